@@ -1,0 +1,235 @@
+/*
+ * libdip -- Dynamic Input Pruning (DIP) and cache-aware masking (DIP-CA) for the
+ * batch-1 SwiGLU MLP forward, native on AMD MI355X (gfx950).
+ *
+ * Paper notation used throughout (Sec. 3-5):
+ *   x        input activations of a linear layer (fp32 here)
+ *   W^u,W^g  up / gate matrices in R^{d_ff x d_model}; W^d down matrix in R^{d_model x d_ff}
+ *   GLU(x)   = W^u x (.) SiLU(W^g x)                                   (Sec. 3, Eq. 2)
+ *   m        binary column mask with exactly k ones, m = topK(s, k)    (Alg. 1)
+ *   c        binary residency mask: which columns are in the cache     (Sec. 5.2)
+ *   s        = |x| (c + gamma (1 - c)) / ||x||_inf                     (Sec. 5.2, Eq. 6)
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is a DEVICE pointer unless its comment says "host".
+ *     Descriptor structs (dip_weight, dip_cache, dip_mlp, dip_debug) are host structs
+ *     holding device pointers; the library reads them during the call only.
+ *   - The library allocates nothing on the device and keeps no device state: outputs,
+ *     cache state and workspace belong to the caller.  It never frees caller memory.
+ *   - All work is enqueued on the caller's stream (a hipStream_t passed as void*, NULL =
+ *     the default stream).  No call synchronises with the host or reads device memory
+ *     back.  Calls on one stream are ordered; calls that share a workspace or a cache on
+ *     different streams race.
+ *   - Arguments are validated on the host before any HIP call.  On an error nothing is
+ *     enqueued and no state changes.  Every function returns a dip_status; the message
+ *     of the last failure on the calling thread is available from dip_last_error().
+ *   - Bit masks: uint32_t[ceil(n/32)], feature i is bit (i & 31) of word (i >> 5); the
+ *     padding bits of the last word are written as zero.  Index lists: int32_t, strictly
+ *     ascending.
+ *   - Weight layout is FEATURE-MAJOR: a matrix the paper writes as W in R^{n_out x n_in}
+ *     is stored as n_in rows of n_out elements; stored row i is the paper's column
+ *     W[:, i], everything that input feature i multiplies, so one selected column is one
+ *     contiguous burst.  Row starts and row_stride_bytes must be multiples of 16.
+ *   - Inputs must be finite.  Non-finite inputs never hang or fault; results are then
+ *     unspecified.
+ */
+#ifndef DIP_H_
+#define DIP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DIP_VERSION_MAJOR 0
+#define DIP_VERSION_MINOR 1
+
+typedef enum dip_status {
+    DIP_OK = 0,
+    DIP_ERR_INVALID_ARG = 1, /* null pointer, k outside [1, n], gamma outside [0, 1], ...   */
+    DIP_ERR_UNSUPPORTED = 2, /* dtype / size / alignment the kernels do not handle          */
+    DIP_ERR_WORKSPACE = 3,   /* workspace pointer null or smaller than *_workspace_bytes()  */
+    DIP_ERR_HIP = 4          /* the HIP runtime reported an error at launch                 */
+} dip_status;
+
+typedef enum dip_dtype {
+    DIP_F32 = 0,      /* fp32 weights                                                       */
+    DIP_BF16 = 1,     /* bfloat16 weights, widened exactly to fp32 before the multiply      */
+    DIP_INT4_G128 = 2 /* signed 4-bit codes, one fp16 scale per 128 consecutive elements of
+                         a stored row, w = scale * q; low nibble = even element.
+                         (Reserved: not implemented by this version.)                       */
+} dip_dtype;
+
+typedef enum dip_policy {
+    DIP_LRU = 0, /* evict the resident whose last use lies farthest back   (Sec. 5.1)       */
+    DIP_LFU = 1  /* evict the resident with the smallest use counter       (Sec. 5.1)       */
+} dip_policy;
+
+/* Largest vector length the selection kernels handle (one workgroup keeps all keys in registers). */
+#define DIP_MAX_N 32768
+
+/* A feature-major weight matrix (see "Weight layout" above). */
+typedef struct dip_weight {
+    const void* data;         /* device; n_in rows                                          */
+    const void* scales;       /* device; fp16 scales for DIP_INT4_G128, otherwise NULL      */
+    int32_t dtype;            /* dip_dtype                                                   */
+    int32_t n_in;             /* input features = stored rows                               */
+    int32_t n_out;            /* outputs = elements per stored row                          */
+    int32_t reserved;         /* must be 0                                                  */
+    int64_t row_stride_bytes; /* distance between stored rows, >= n_out * element size      */
+} dip_weight;
+
+/* The three matrices of one SwiGLU MLP (Sec. 3, Eq. 1-2).  Up and gate are bundled per
+ * input feature: stored row i of w_ug is [ W^u[:, i] ; W^g[:, i] ], 2*d_ff elements, so
+ * w_ug.n_in = d_model, w_ug.n_out = 2*d_ff, and w_d.n_in = d_ff, w_d.n_out = d_model. */
+typedef struct dip_mlp {
+    dip_weight w_ug;
+    dip_weight w_d;
+} dip_mlp;
+
+#define DIP_CACHE_META_WORDS 8
+/* meta[] layout (device, uint32): */
+#define DIP_META_STEP 0      /* 1-based step counter t; advanced by one per update          */
+#define DIP_META_RESIDENT 1  /* number of resident columns after the last update            */
+#define DIP_META_HITS 2      /* |m & c| of the last update                                  */
+#define DIP_META_INSERTED 3  /* misses brought into the cache by the last update            */
+#define DIP_META_EVICTED 4   /* residents evicted by the last update                        */
+#define DIP_META_BYPASSED 5  /* misses that found no room and were not cached               */
+#define DIP_META_CUM_HITS 6  /* running sum of hits   (wraps at 2^32)                       */
+#define DIP_META_CUM_LOOKUPS 7 /* running sum of |m|  (wraps at 2^32)                       */
+
+/* Residency state of one linear layer's columns (the paper's c, Sec. 5.2), owned by the caller. */
+typedef struct dip_cache {
+    uint32_t* bits;   /* device; ceil(n/32) words; bit set = column resident                */
+    uint32_t* stamp;  /* device; n words; LRU: step of last use, LFU: use count             */
+    uint32_t* meta;   /* device; DIP_CACHE_META_WORDS words                                 */
+    int32_t n;        /* number of columns (input features of the layer)                   */
+    int32_t capacity; /* at most this many columns resident, 0 <= capacity <= n             */
+    int32_t policy;   /* dip_policy                                                         */
+    int32_t reserved; /* must be 0                                                          */
+} dip_cache;
+
+/* Optional per-stage outputs of dip_swiglu_mlp_forward for stage-wise comparison; every
+ * member may be NULL. */
+typedef struct dip_debug {
+    float* s_in;        /* d_model scores at pruning point 1                                */
+    uint32_t* mask_in;  /* ceil(d_model/32) words                                           */
+    int32_t* idx_in;    /* k_in ascending indices                                           */
+    float* h;           /* d_ff: the sparse GLU output  GLU~(x)                             */
+    float* s_mid;       /* d_ff scores at pruning point 2                                   */
+    uint32_t* mask_mid; /* ceil(d_ff/32) words                                              */
+    int32_t* idx_mid;   /* k_mid ascending indices                                          */
+} dip_debug;
+
+/* (major << 16) | minor. */
+int32_t dip_version(void);
+
+/* Message of the last failing call on this thread (host string, never NULL, owned by the library). */
+const char* dip_last_error(void);
+
+/*
+ * Cache-aware scores, Sec. 5.2 Eq. 6 / Alg. 1 step 1, in fp32 with this exact operation
+ * order (round to nearest even, no fused operations, denormals kept):
+ *     a = |x_i| ;  p = c_i ? a : fl(a * gamma) ;  s_i = fl(p / M),  M = max_i |x_i| ;
+ *     M == 0  ->  s = 0.
+ * cache_bits == NULL selects the plain DIP key of Sec. 4:  s_i = |x_i|  (gamma ignored).
+ *   x          n floats          cache_bits  ceil(n/32) words or NULL
+ *   s_out      n floats          1 <= n <= DIP_MAX_N,  0 <= gamma <= 1
+ */
+int32_t dip_ca_scores(const float* x, int32_t n, const uint32_t* cache_bits, float gamma,
+                      float* s_out, void* stream);
+
+/*
+ * m = topK(s, k), Alg. 1 step 2 (per-token top-K thresholding, Sec. 3.1): exactly k
+ * features with the largest keys; among equal keys the lowest index wins.  Keys must be
+ * non-negative (scores are).
+ *   s         n floats, 1 <= k <= n <= DIP_MAX_N
+ *   mask_out  ceil(n/32) words, or NULL
+ *   idx_out   k ascending indices, or NULL      (at least one of the two outputs is required)
+ */
+int32_t dip_prune_topk(const float* s, int32_t n, int32_t k, uint32_t* mask_out,
+                       int32_t* idx_out, void* stream);
+
+/*
+ * Start a cache: step counter 1, all counters 0, stamps 0, residency = initial_bits
+ * (ceil(n/32) words with at most `capacity` bits set -- not checked on the device; padding
+ * bits must be zero) or empty when initial_bits is NULL.
+ */
+int32_t dip_cache_init(const dip_cache* cache, const uint32_t* initial_bits, void* stream);
+
+/*
+ * c' = cache_update(c, m), Alg. 1 step 3, for one token's mask m (ceil(n/32) words).
+ * The mask is a set, so the update is set-valued and deterministic:
+ *   hits   = m & c   keep their place; LRU stamps them with the current step
+ *   misses = m & ~c  in ascending index order
+ *   free   = capacity - |c| ;  victims V = c & ~m  (a column this token uses is never evicted)
+ *   n_ins  = min(|misses|, free + |V|) ;  evict the max(0, n_ins - free) members of V with
+ *            the smallest (stamp, index) ;  insert the first n_ins misses ;  the remaining
+ *            misses bypass the cache (Sec. 6.3: when the active set does not fit, part of
+ *            it is used without being cached).
+ *   LFU: stamp counts every selection of a column, resident or not, and survives eviction.
+ * Advances meta[DIP_META_STEP] and refreshes the other meta counters.
+ */
+int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void* stream);
+
+/*
+ * Column-gathered matrix-vector product, Alg. 1 step 4 (W~ = W (.) m) applied to x:
+ *     y[j] = sum_{t<k} W[j, idx[t]] * x[idx[t]]        fp32 accumulation.
+ * The summation order is fixed by the launch configuration, so results are bit-repeatable.
+ *   w        feature-major matrix (F32 or BF16); n_out % (16 / element size) == 0
+ *   x        w->n_in floats        idx   k ascending indices in [0, n_in), 1 <= k <= n_in
+ *   y_out    w->n_out floats       ws    dip_gathered_gemv_workspace_bytes() bytes, 256-aligned
+ */
+size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k);
+int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* idx, int32_t k,
+                          float* y_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One token through one DIP / DIP-CA SwiGLU MLP (Sec. 4 composed with Alg. 1 at both
+ * pruning points):
+ *   1. s1 = score(x, c_in)          m1 = topK(s1, k_in)       c_in  <- cache_update(c_in,  m1)
+ *   2. h~ = (sum_{i in m1} W^u[:,i] x_i) (.) SiLU(sum_{i in m1} W^g[:,i] x_i)
+ *   3. s2 = score(h~, c_mid)        m2 = topK(s2, k_mid)      c_mid <- cache_update(c_mid, m2)
+ *   4. y  = sum_{i in m2} W^d[:,i] h~_i
+ * Scoring uses the cache state from before this token (the paper's c^(t-1)).  With a NULL
+ * cache the key is |.| (DIP); a cache pointer switches that point to Eq. 6 (DIP-CA) and its
+ * state is updated in place.
+ *   x      d_model floats       y_out   d_model floats
+ *   1 <= k_in <= d_model, 1 <= k_mid <= d_ff;  d_model, d_ff <= DIP_MAX_N
+ *   dbg    NULL or stage outputs           ws   *_workspace_bytes() bytes, 256-aligned
+ */
+size_t dip_swiglu_mlp_forward_workspace_bytes(const dip_mlp* mlp, int32_t k_in, int32_t k_mid);
+int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                               const dip_cache* cache_in, const dip_cache* cache_mid,
+                               float gamma, float* y_out, const dip_debug* dbg, void* ws,
+                               size_t ws_bytes, void* stream);
+
+/*
+ * The same forward for n_layers independent layers in one call (a decode step over a
+ * stack): layer l reads x + l * x_stride and writes y_out + l * y_stride (strides in
+ * floats).  mlps / caches_in / caches_mid are host arrays of n_layers descriptors; the
+ * cache arrays may be NULL (DIP) .  All layers share one workspace sized for the largest.
+ */
+int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,
+                                     int64_t x_stride, int32_t k_in, int32_t k_mid,
+                                     const dip_cache* caches_in, const dip_cache* caches_mid,
+                                     float gamma, float* y_out, int64_t y_stride, void* ws,
+                                     size_t ws_bytes, void* stream);
+
+/*
+ * Launch-shape override for the gathered GEMV kernels, for tuning sweeps.  0 restores the
+ * built-in choice for that parameter.  Host-side, process-wide, not thread-safe against
+ * concurrent launches.
+ *   lanes_per_row  8, 16, 32 or 64 lanes cooperate on one stored row (16 bytes per lane)
+ *   waves          wavefronts per workgroup: 2, 4, 8 or 16
+ *   ksplit         workgroups that share one output strip (partial sums reduced in fixed order)
+ *   unroll         rows in flight per lane group: 1, 2, 4 or 8
+ */
+int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIP_H_ */

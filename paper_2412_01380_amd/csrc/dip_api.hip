@@ -1,0 +1,345 @@
+// C ABI of libdip: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates device memory, synchronises, or reads device data.
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "dip_internal.h"
+
+namespace dip {
+
+static thread_local char t_err[512] = "";
+
+int32_t fail(int32_t status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_err, sizeof(t_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int32_t check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return DIP_OK;
+    return fail(DIP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int elem_bytes(int dtype) { return dtype == DIP_F32 ? 4 : 2; }
+
+int32_t validate_weight(const dip_weight* w, const char* name) {
+    if (!w) return fail(DIP_ERR_INVALID_ARG, "%s: null descriptor", name);
+    if (!w->data) return fail(DIP_ERR_INVALID_ARG, "%s: null data pointer", name);
+    if (w->n_in < 1 || w->n_out < 1) return fail(DIP_ERR_INVALID_ARG, "%s: n_in and n_out must be >= 1", name);
+    if (w->reserved != 0) return fail(DIP_ERR_INVALID_ARG, "%s: reserved must be 0", name);
+    if (w->dtype == DIP_INT4_G128) return fail(DIP_ERR_UNSUPPORTED, "%s: int4 weights are not implemented", name);
+    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16) return fail(DIP_ERR_UNSUPPORTED, "%s: unknown dtype %d", name, w->dtype);
+    const int eb = elem_bytes(w->dtype);
+    if (w->n_out % (16 / eb)) return fail(DIP_ERR_UNSUPPORTED, "%s: n_out must be a multiple of %d", name, 16 / eb);
+    if (w->row_stride_bytes < (int64_t)w->n_out * eb)
+        return fail(DIP_ERR_INVALID_ARG, "%s: row_stride_bytes smaller than a row", name);
+    if (w->row_stride_bytes % 16 || !aligned(w->data, 16))
+        return fail(DIP_ERR_UNSUPPORTED, "%s: rows must start on 16-byte boundaries", name);
+    return DIP_OK;
+}
+
+int32_t validate_cache(const dip_cache* c, int n, const char* name) {
+    if (!c->bits || !c->stamp || !c->meta) return fail(DIP_ERR_INVALID_ARG, "%s: null state pointer", name);
+    if (c->n < 1 || c->n > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "%s: n must be in [1, %d]", name, DIP_MAX_N);
+    if (n >= 0 && c->n != n) return fail(DIP_ERR_INVALID_ARG, "%s: cache covers %d columns, layer has %d", name, c->n, n);
+    if (c->capacity < 0 || c->capacity > c->n) return fail(DIP_ERR_INVALID_ARG, "%s: capacity outside [0, n]", name);
+    if (c->policy != DIP_LRU && c->policy != DIP_LFU) return fail(DIP_ERR_INVALID_ARG, "%s: unknown policy", name);
+    if (c->reserved != 0) return fail(DIP_ERR_INVALID_ARG, "%s: reserved must be 0", name);
+    return DIP_OK;
+}
+
+int32_t validate_gamma(float gamma) {
+    if (!std::isfinite(gamma) || gamma < 0.f || gamma > 1.f)
+        return fail(DIP_ERR_INVALID_ARG, "gamma must be finite and within [0, 1]");
+    return DIP_OK;
+}
+
+// ---- workspace layout of the fused forward ------------------------------------------------
+struct ForwardPlan {
+    int d, f;
+    GemvShape ug, dn;
+    int strips_ug, strips_dn;
+    size_t off_idx1, off_val1, off_h, off_idx2, off_val2, off_part_ug, off_part_dn, off_cnt;
+    size_t total;
+};
+
+ForwardPlan plan_forward(const dip_mlp* mlp, int k_in, int k_mid) {
+    ForwardPlan pl;
+    pl.d = mlp->w_ug.n_in;
+    pl.f = mlp->w_d.n_in;
+    pl.ug = choose_gemv_shape(mlp->w_ug.dtype, pl.f, 2, k_in);
+    pl.dn = choose_gemv_shape(mlp->w_d.dtype, pl.d, 1, k_mid);
+    pl.strips_ug = gemv_strips(pl.ug, mlp->w_ug.dtype, pl.f);
+    pl.strips_dn = gemv_strips(pl.dn, mlp->w_d.dtype, pl.d);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    pl.off_idx1 = take(sizeof(int32_t) * k_in);
+    pl.off_val1 = take(sizeof(float) * k_in);
+    pl.off_h = take(sizeof(float) * pl.f);
+    pl.off_idx2 = take(sizeof(int32_t) * k_mid);
+    pl.off_val2 = take(sizeof(float) * k_mid);
+    pl.off_part_ug = take(pl.ug.ksplit > 1 ? sizeof(float) * 2 * pl.f * pl.ug.ksplit : 0);
+    pl.off_part_dn = take(pl.dn.ksplit > 1 ? sizeof(float) * pl.d * pl.dn.ksplit : 0);
+    pl.off_cnt = take(sizeof(uint32_t) * (pl.strips_ug + pl.strips_dn));
+    pl.total = o;
+    return pl;
+}
+
+int32_t validate_mlp(const dip_mlp* mlp, int k_in, int k_mid) {
+    if (!mlp) return fail(DIP_ERR_INVALID_ARG, "mlp: null descriptor");
+    int32_t st = validate_weight(&mlp->w_ug, "w_ug");
+    if (st) return st;
+    st = validate_weight(&mlp->w_d, "w_d");
+    if (st) return st;
+    const int d = mlp->w_ug.n_in, f = mlp->w_d.n_in;
+    if (mlp->w_ug.n_out != 2 * f) return fail(DIP_ERR_INVALID_ARG, "w_ug.n_out must be 2 * w_d.n_in (bundled up/gate)");
+    if (mlp->w_d.n_out != d) return fail(DIP_ERR_INVALID_ARG, "w_d.n_out must equal w_ug.n_in");
+    if (d > DIP_MAX_N || f > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "d_model and d_ff must be <= %d", DIP_MAX_N);
+    const int eb = elem_bytes(mlp->w_ug.dtype);
+    if (f % (16 / eb)) return fail(DIP_ERR_UNSUPPORTED, "d_ff must be a multiple of %d", 16 / eb);
+    if (k_in < 1 || k_in > d) return fail(DIP_ERR_INVALID_ARG, "k_in must be in [1, d_model]");
+    if (k_mid < 1 || k_mid > f) return fail(DIP_ERR_INVALID_ARG, "k_mid must be in [1, d_ff]");
+    return DIP_OK;
+}
+
+int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, int k_in, int k_mid,
+                    const dip_cache* cin, const dip_cache* cmid, float gamma, float* y,
+                    const dip_debug* dbg, char* ws, hipStream_t stream) {
+    int32_t* idx1 = reinterpret_cast<int32_t*>(ws + pl.off_idx1);
+    float* val1 = reinterpret_cast<float*>(ws + pl.off_val1);
+    float* h = reinterpret_cast<float*>(ws + pl.off_h);
+    int32_t* idx2 = reinterpret_cast<int32_t*>(ws + pl.off_idx2);
+    float* val2 = reinterpret_cast<float*>(ws + pl.off_val2);
+    float* part_ug = reinterpret_cast<float*>(ws + pl.off_part_ug);
+    float* part_dn = reinterpret_cast<float*>(ws + pl.off_part_dn);
+    uint32_t* cnt_ug = reinterpret_cast<uint32_t*>(ws + pl.off_cnt);
+    uint32_t* cnt_dn = cnt_ug + pl.strips_ug;
+    if (dbg && dbg->idx_in) idx1 = dbg->idx_in;
+    if (dbg && dbg->idx_mid) idx2 = dbg->idx_mid;
+    if (dbg && dbg->h) h = dbg->h;
+
+    // point 1: scores, m1, cache update
+    SelectParams s1;
+    std::memset(&s1, 0, sizeof(s1));
+    s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
+    s1.s_out = dbg ? dbg->s_in : nullptr;
+    s1.mask_out = dbg ? dbg->mask_in : nullptr;
+    s1.idx_out = idx1; s1.val_out = val1;
+    if (cin) {
+        s1.score_bits = cin->bits; s1.c_bits = cin->bits; s1.c_stamp = cin->stamp; s1.c_meta = cin->meta;
+        s1.capacity = cin->capacity; s1.policy = cin->policy;
+    }
+    s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
+    int32_t st = check_hip(launch_select(s1, stream), "select (point 1)");
+    if (st) return st;
+
+    // gathered up/gate GEMV + SwiGLU
+    GemvParams g1;
+    std::memset(&g1, 0, sizeof(g1));
+    g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes; g1.dtype = mlp->w_ug.dtype;
+    g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.idx = idx1; g1.val = val1; g1.k = k_in; g1.out = h;
+    g1.partial = part_ug; g1.counters = cnt_ug;
+    st = check_hip(launch_gemv(g1, pl.ug, stream), "gathered GEMV (up/gate)");
+    if (st) return st;
+
+    // point 2
+    SelectParams s2;
+    std::memset(&s2, 0, sizeof(s2));
+    s2.v = h; s2.n = pl.f; s2.k = k_mid; s2.gamma = gamma;
+    s2.s_out = dbg ? dbg->s_mid : nullptr;
+    s2.mask_out = dbg ? dbg->mask_mid : nullptr;
+    s2.idx_out = idx2; s2.val_out = val2;
+    if (cmid) {
+        s2.score_bits = cmid->bits; s2.c_bits = cmid->bits; s2.c_stamp = cmid->stamp; s2.c_meta = cmid->meta;
+        s2.capacity = cmid->capacity; s2.policy = cmid->policy;
+    }
+    st = check_hip(launch_select(s2, stream), "select (point 2)");
+    if (st) return st;
+
+    // gathered down GEMV
+    GemvParams g2;
+    std::memset(&g2, 0, sizeof(g2));
+    g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes; g2.dtype = mlp->w_d.dtype;
+    g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.idx = idx2; g2.val = val2; g2.k = k_mid; g2.out = y;
+    g2.partial = part_dn; g2.counters = cnt_dn;
+    return check_hip(launch_gemv(g2, pl.dn, stream), "gathered GEMV (down)");
+}
+
+}  // namespace
+}  // namespace dip
+
+using namespace dip;
+
+extern "C" {
+
+int32_t dip_version(void) { return (DIP_VERSION_MAJOR << 16) | DIP_VERSION_MINOR; }
+
+const char* dip_last_error(void) { return t_err; }
+
+int32_t dip_ca_scores(const float* x, int32_t n, const uint32_t* cache_bits, float gamma,
+                      float* s_out, void* stream) {
+    if (!x || !s_out) return fail(DIP_ERR_INVALID_ARG, "dip_ca_scores: null pointer");
+    if (n < 1) return fail(DIP_ERR_INVALID_ARG, "dip_ca_scores: n must be >= 1");
+    if (n > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "dip_ca_scores: n must be <= %d", DIP_MAX_N);
+    if (cache_bits) {
+        int32_t st = validate_gamma(gamma);
+        if (st) return st;
+    }
+    SelectParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.v = x; p.n = n; p.k = 1; p.score_bits = cache_bits; p.gamma = gamma;
+    p.scores_only = 1; p.s_out = s_out;
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_ca_scores");
+}
+
+int32_t dip_prune_topk(const float* s, int32_t n, int32_t k, uint32_t* mask_out, int32_t* idx_out,
+                       void* stream) {
+    if (!s) return fail(DIP_ERR_INVALID_ARG, "dip_prune_topk: null input");
+    if (!mask_out && !idx_out) return fail(DIP_ERR_INVALID_ARG, "dip_prune_topk: no output requested");
+    if (n < 1) return fail(DIP_ERR_INVALID_ARG, "dip_prune_topk: n must be >= 1");
+    if (n > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "dip_prune_topk: n must be <= %d", DIP_MAX_N);
+    if (k < 1 || k > n) return fail(DIP_ERR_INVALID_ARG, "dip_prune_topk: k must be in [1, n]");
+    SelectParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.v = s; p.n = n; p.k = k; p.mask_out = mask_out; p.idx_out = idx_out;
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_prune_topk");
+}
+
+int32_t dip_cache_init(const dip_cache* cache, const uint32_t* initial_bits, void* stream) {
+    if (!cache) return fail(DIP_ERR_INVALID_ARG, "dip_cache_init: null descriptor");
+    int32_t st = validate_cache(cache, -1, "dip_cache_init");
+    if (st) return st;
+    CacheInitParams p{cache->bits, cache->stamp, cache->meta, initial_bits, cache->n};
+    return check_hip(launch_cache_init(p, static_cast<hipStream_t>(stream)), "dip_cache_init");
+}
+
+int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void* stream) {
+    if (!cache) return fail(DIP_ERR_INVALID_ARG, "dip_cache_update: null descriptor");
+    if (!mask_bits) return fail(DIP_ERR_INVALID_ARG, "dip_cache_update: null mask");
+    int32_t st = validate_cache(cache, -1, "dip_cache_update");
+    if (st) return st;
+    SelectParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.n = cache->n; p.k = 1; p.mask_in = mask_bits;
+    p.c_bits = cache->bits; p.c_stamp = cache->stamp; p.c_meta = cache->meta;
+    p.capacity = cache->capacity; p.policy = cache->policy;
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_cache_update");
+}
+
+size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k) {
+    if (!w || w->n_out < 1 || k < 1) return 0;
+    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16) return 0;
+    const GemvShape s = choose_gemv_shape(w->dtype, w->n_out, 1, k);
+    const int strips = gemv_strips(s, w->dtype, w->n_out);
+    size_t bytes = align_up(sizeof(uint32_t) * strips, 256);
+    if (s.ksplit > 1) bytes += align_up(sizeof(float) * (size_t)w->n_out * s.ksplit, 256);
+    return bytes;
+}
+
+int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* idx, int32_t k,
+                          float* y_out, void* ws, size_t ws_bytes, void* stream) {
+    int32_t st = validate_weight(w, "dip_gathered_gemv");
+    if (st) return st;
+    if (!x || !idx || !y_out) return fail(DIP_ERR_INVALID_ARG, "dip_gathered_gemv: null pointer");
+    if (k < 1 || k > w->n_in) return fail(DIP_ERR_INVALID_ARG, "dip_gathered_gemv: k must be in [1, n_in]");
+    const size_t need = dip_gathered_gemv_workspace_bytes(w, k);
+    if (!ws || ws_bytes < need || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "dip_gathered_gemv: workspace must be 256-aligned and >= %zu bytes", need);
+    const GemvShape s = choose_gemv_shape(w->dtype, w->n_out, 1, k);
+    const int strips = gemv_strips(s, w->dtype, w->n_out);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(base);
+    float* partial = reinterpret_cast<float*>(base + align_up(sizeof(uint32_t) * strips, 256));
+    if (s.ksplit > 1) {
+        st = check_hip(launch_zero_u32(counters, strips, hs), "dip_gathered_gemv: counter reset");
+        if (st) return st;
+    }
+    GemvParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.w = w->data; p.row_stride = w->row_stride_bytes; p.dtype = w->dtype; p.n_in = w->n_in; p.n_out = w->n_out;
+    p.nseg = 1; p.idx = idx; p.val = nullptr; p.x_full = x; p.k = k; p.out = y_out;
+    p.partial = partial; p.counters = counters;
+    return check_hip(launch_gemv(p, s, hs), "dip_gathered_gemv");
+}
+
+size_t dip_swiglu_mlp_forward_workspace_bytes(const dip_mlp* mlp, int32_t k_in, int32_t k_mid) {
+    if (validate_mlp(mlp, k_in, k_mid)) return 0;
+    return plan_forward(mlp, k_in, k_mid).total;
+}
+
+static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const float* x, int64_t x_stride,
+                               int32_t k_in, int32_t k_mid, const dip_cache* caches_in,
+                               const dip_cache* caches_mid, float gamma, float* y_out,
+                               int64_t y_stride, const dip_debug* dbg, void* ws, size_t ws_bytes,
+                               void* stream) {
+    if (!mlps) return fail(DIP_ERR_INVALID_ARG, "forward: null mlp descriptor");
+    if (n_layers < 1) return fail(DIP_ERR_INVALID_ARG, "forward: n_layers must be >= 1");
+    if (!x || !y_out) return fail(DIP_ERR_INVALID_ARG, "forward: null x or y_out");
+    if (caches_in || caches_mid) {
+        int32_t st = validate_gamma(gamma);
+        if (st) return st;
+    }
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        int32_t st = validate_mlp(&mlps[l], k_in, k_mid);
+        if (st) return st;
+        if (caches_in && (st = validate_cache(&caches_in[l], mlps[l].w_ug.n_in, "cache_in"))) return st;
+        if (caches_mid && (st = validate_cache(&caches_mid[l], mlps[l].w_d.n_in, "cache_mid"))) return st;
+        const size_t t = plan_forward(&mlps[l], k_in, k_mid).total;
+        if (t > need) need = t;
+    }
+    if (!ws || ws_bytes < need || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "forward: workspace must be 256-aligned and >= %zu bytes", need);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    for (int l = 0; l < n_layers; ++l) {
+        const ForwardPlan pl = plan_forward(&mlps[l], k_in, k_mid);
+        int32_t st = forward_one(&mlps[l], pl, x + (int64_t)l * x_stride, k_in, k_mid,
+                                 caches_in ? &caches_in[l] : nullptr,
+                                 caches_mid ? &caches_mid[l] : nullptr, gamma,
+                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs);
+        if (st) return st;
+    }
+    return DIP_OK;
+}
+
+int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                               const dip_cache* cache_in, const dip_cache* cache_mid, float gamma,
+                               float* y_out, const dip_debug* dbg, void* ws, size_t ws_bytes,
+                               void* stream) {
+    return forward_checked(mlp, 1, x, 0, k_in, k_mid, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
+                           ws_bytes, stream);
+}
+
+int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,
+                                     int64_t x_stride, int32_t k_in, int32_t k_mid,
+                                     const dip_cache* caches_in, const dip_cache* caches_mid,
+                                     float gamma, float* y_out, int64_t y_stride, void* ws,
+                                     size_t ws_bytes, void* stream) {
+    return forward_checked(mlps, n_layers, x, x_stride, k_in, k_mid, caches_in, caches_mid, gamma,
+                           y_out, y_stride, nullptr, ws, ws_bytes, stream);
+}
+
+int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll) {
+    auto in = [](int v, std::initializer_list<int> ok) {
+        for (int o : ok) if (v == o) return true;
+        return false;
+    };
+    if (!in(lanes_per_row, {0, 8, 16, 32, 64})) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: lanes_per_row");
+    if (!in(waves, {0, 2, 4, 8, 16})) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: waves");
+    if (!in(unroll, {0, 1, 2, 4, 8})) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: unroll");
+    if (ksplit < 0 || ksplit > 4096) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: ksplit");
+    g_gemv_override = GemvShape{lanes_per_row, waves, ksplit, unroll};
+    return DIP_OK;
+}
+
+}  // extern "C"

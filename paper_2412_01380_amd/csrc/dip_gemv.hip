@@ -1,0 +1,283 @@
+// Column-gathered GEMV (Alg. 1 step 4 applied to x; Sec. 4 for the bundled up/gate case):
+//     y[j] = sum_{t<k} W[j, idx[t]] * x[idx[t]]
+// over a feature-major matrix, so each selected column is one contiguous row in HBM.
+//
+// Decode at batch 1 reads every selected weight exactly once and does two flops per
+// element: the kernel is bound by HBM bandwidth, not arithmetic, so there are no matrix
+// cores here -- only wide coalesced loads, many of them in flight, and fp32 FMAs.
+//
+// Work split.  The outputs are cut into strips of LPR*EPL columns (EPL = elements per
+// 16-byte load).  A workgroup owns one strip (both the up and the gate strip when the
+// matrix is the bundled pair) and a contiguous share of the k selected rows; inside it
+// every wavefront handles 64/LPR rows per step, LPR lanes side by side on one row, each
+// lane loading 16 bytes.  Sums are combined in a fixed order: lane groups inside a
+// wavefront (xor butterfly), wavefronts through LDS in index order, workgroups of one
+// strip through a partial buffer that the last workgroup to arrive adds in index order.
+// The result is bit-repeatable for a given launch shape.
+
+#include "dip_internal.h"
+
+namespace dip {
+
+GemvShape g_gemv_override = {0, 0, 0, 0};
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename WT>
+struct Elem;
+template <>
+struct Elem<float> {
+    static constexpr int kPerLoad = 4;
+    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[4]) {
+        f[0] = __uint_as_float(q.x);
+        f[1] = __uint_as_float(q.y);
+        f[2] = __uint_as_float(q.z);
+        f[3] = __uint_as_float(q.w);
+    }
+};
+template <>
+struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
+    static constexpr int kPerLoad = 8;
+    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[8]) {
+        f[0] = __uint_as_float(q.x << 16);
+        f[1] = __uint_as_float(q.x & 0xffff0000u);
+        f[2] = __uint_as_float(q.y << 16);
+        f[3] = __uint_as_float(q.y & 0xffff0000u);
+        f[4] = __uint_as_float(q.z << 16);
+        f[5] = __uint_as_float(q.z & 0xffff0000u);
+        f[6] = __uint_as_float(q.w << 16);
+        f[7] = __uint_as_float(q.w & 0xffff0000u);
+    }
+};
+
+__device__ __forceinline__ u32x4 load16(const char* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+__device__ __forceinline__ float silu(float g) { return g / (1.0f + expf(-g)); }
+
+template <typename WT, int LPR, int WAVES, int UNROLL, int NSEG>
+__global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
+    constexpr int EPL = Elem<WT>::kPerLoad;
+    constexpr int RPW = 64 / LPR;          // rows per wavefront step
+    constexpr int SC = LPR * EPL;          // strip columns
+    constexpr int ROWS_PER_STEP = WAVES * RPW;
+    __shared__ float red[WAVES][NSEG][SC];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane / LPR, l = lane % LPR;
+    const int strip = blockIdx.x;
+    const int g = blockIdx.y, G = gridDim.y;
+    const int col = strip * SC + l * EPL;
+    const bool col_ok = col < p.n_out;
+
+    // this workgroup's share of the selected rows
+    const int kb = (int)(((int64_t)p.k * g) / G);
+    const int ke = (int)(((int64_t)p.k * (g + 1)) / G);
+
+    float acc[NSEG][EPL];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[s][e] = 0.f;
+
+    const char* wbase = static_cast<const char*>(p.w) + (size_t)col * sizeof(WT);
+    const size_t seg_bytes = (size_t)p.n_out * sizeof(WT);
+
+    for (int t0 = kb + wave * RPW + sub; t0 < ke; t0 += UNROLL * ROWS_PER_STEP) {
+        int row[UNROLL];
+        float xv[UNROLL];
+        u32x4 q[UNROLL][NSEG];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int t = t0 + u * ROWS_PER_STEP;
+            const bool ok = t < ke;
+            row[u] = ok ? p.idx[t] : -1;
+            if ((unsigned)row[u] >= (unsigned)p.n_in) row[u] = -1;  // an index outside the matrix contributes nothing
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int t = t0 + u * ROWS_PER_STEP;
+            xv[u] = 0.f;
+            if (row[u] >= 0) xv[u] = p.val ? p.val[t] : p.x_full[row[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                q[u][s] = u32x4{0u, 0u, 0u, 0u};
+                if (row[u] >= 0 && col_ok)
+                    q[u][s] = load16(wbase + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                float f[EPL];
+                Elem<WT>::widen(q[u][s], f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], xv[u], acc[s][e]);
+            }
+        }
+    }
+
+    // lane groups of one wavefront
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[s][e] += __shfl_xor(acc[s][e], off);
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) red[wave][s][l * EPL + e] = acc[s][e];
+    }
+    __syncthreads();
+
+    // wavefronts of one workgroup: lane c of the first NSEG*SC lanes owns one output
+    constexpr int NOUT = NSEG * SC;
+    static_assert(NOUT <= WAVES * 64, "strip wider than the workgroup");  // launch_nseg guards this
+    const int oseg = tid / SC, ocol = tid % SC;
+    const int gcol = strip * SC + ocol;
+    const bool owner = tid < NOUT && gcol < p.n_out;
+    float sum = 0.f;
+    if (owner) {
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w][oseg][ocol];
+    }
+
+    if (G > 1) {
+        // workgroups of one strip
+        float* part = p.partial + ((size_t)g * NSEG + oseg) * (size_t)p.n_out + gcol;
+        if (owner) __hip_atomic_store(part, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(&p.counters[strip], 1u, __ATOMIC_ACQ_REL,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev == (uint32_t)(G - 1));
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __threadfence();
+        sum = 0.f;
+        if (owner) {
+            for (int gg = 0; gg < G; ++gg) {
+                const float* src = p.partial + ((size_t)gg * NSEG + oseg) * (size_t)p.n_out + gcol;
+                sum += __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+
+    if constexpr (NSEG == 2) {
+        // Sec. 3 Eq. 2: GLU = up (.) SiLU(gate); the gate sums sit SC lanes further on
+        __syncthreads();
+        if (owner) red[0][oseg][ocol] = sum;
+        __syncthreads();
+        if (owner && oseg == 0) p.out[gcol] = red[0][0][ocol] * silu(red[0][1][ocol]);
+    } else {
+        if (owner) p.out[gcol] = sum;
+    }
+}
+
+template <typename WT, int LPR, int WAVES, int UNROLL>
+hipError_t launch_nseg(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+    constexpr int SC = LPR * Elem<WT>::kPerLoad;
+    const int strips = (p.n_out + SC - 1) / SC;
+    dim3 grid(strips, s.ksplit), block(WAVES * 64);
+    if (p.nseg == 2) {
+        if constexpr (2 * SC <= WAVES * 64) {
+            hipLaunchKernelGGL((gemv_kernel<WT, LPR, WAVES, UNROLL, 2>), grid, block, 0, stream, p);
+        } else {
+            return hipErrorInvalidConfiguration;
+        }
+    } else {
+        if constexpr (SC <= WAVES * 64) {
+            hipLaunchKernelGGL((gemv_kernel<WT, LPR, WAVES, UNROLL, 1>), grid, block, 0, stream, p);
+        } else {
+            return hipErrorInvalidConfiguration;
+        }
+    }
+    return hipGetLastError();
+}
+
+template <typename WT, int LPR, int WAVES>
+hipError_t launch_unroll(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+    switch (s.unroll) {
+        case 1: return launch_nseg<WT, LPR, WAVES, 1>(p, s, stream);
+        case 2: return launch_nseg<WT, LPR, WAVES, 2>(p, s, stream);
+        case 4: return launch_nseg<WT, LPR, WAVES, 4>(p, s, stream);
+        case 8: return launch_nseg<WT, LPR, WAVES, 8>(p, s, stream);
+    }
+    return hipErrorInvalidConfiguration;
+}
+
+template <typename WT, int LPR>
+hipError_t launch_waves(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+    switch (s.waves) {
+        case 2: return launch_unroll<WT, LPR, 2>(p, s, stream);
+        case 4: return launch_unroll<WT, LPR, 4>(p, s, stream);
+        case 8: return launch_unroll<WT, LPR, 8>(p, s, stream);
+        case 16: return launch_unroll<WT, LPR, 16>(p, s, stream);
+    }
+    return hipErrorInvalidConfiguration;
+}
+
+template <typename WT>
+hipError_t launch_lpr(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+    switch (s.lpr) {
+        case 8: return launch_waves<WT, 8>(p, s, stream);
+        case 16: return launch_waves<WT, 16>(p, s, stream);
+        case 32: return launch_waves<WT, 32>(p, s, stream);
+        case 64: return launch_waves<WT, 64>(p, s, stream);
+    }
+    return hipErrorInvalidConfiguration;
+}
+
+}  // namespace
+
+int gemv_strips(const GemvShape& s, int dtype, int n_out) {
+    const int epl = dtype == DIP_F32 ? 4 : 8;
+    const int sc = s.lpr * epl;
+    return (n_out + sc - 1) / sc;
+}
+
+GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
+    GemvShape s;
+    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : 8;
+    s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
+    s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
+    // a bundled strip needs 2*SC lanes for its epilogue
+    const int epl = dtype == DIP_F32 ? 4 : 8;
+    while (nseg * s.lpr * epl > s.waves * 64 && s.waves < 16) s.waves *= 2;
+    if (g_gemv_override.ksplit) {
+        s.ksplit = g_gemv_override.ksplit;
+    } else {
+        // aim for about four workgroups per compute unit
+        const int strips = gemv_strips(s, dtype, n_out);
+        int ks = (1024 + strips - 1) / strips;
+        if (ks < 1) ks = 1;
+        // keep at least one full step of rows per workgroup
+        const int rows_per_step = s.waves * (64 / s.lpr);
+        while (ks > 1 && k / ks < rows_per_step) --ks;
+        s.ksplit = ks;
+    }
+    if (s.ksplit > k) s.ksplit = k;
+    if (s.ksplit < 1) s.ksplit = 1;
+    return s;
+}
+
+hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+    if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream);
+    if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dip

@@ -1,0 +1,88 @@
+// Internal declarations shared by the libdip translation units (not part of the C ABI).
+#ifndef DIP_INTERNAL_H_
+#define DIP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dip.h"
+
+namespace dip {
+
+// ---- error reporting -------------------------------------------------------------------
+int32_t fail(int32_t status, const char* fmt, ...);
+int32_t check_hip(hipError_t e, const char* what);
+
+// ---- selection kernel (scores -> top-K -> cache update), one workgroup ------------------
+constexpr int kSelThreads = 1024;
+
+struct SelectParams {
+    const float* v;               // input vector (x or h~), n floats
+    int n;
+    int k;
+    const uint32_t* score_bits;   // residency used for scoring (Eq. 6), or null for |v|
+    float gamma;
+    const uint32_t* mask_in;      // non-null: take the mask from here instead of selecting
+    int scores_only;              // 1: write s_out and return
+    float* s_out;                 // nullable
+    uint32_t* mask_out;           // nullable
+    int32_t* idx_out;             // nullable, k entries
+    float* val_out;               // nullable, k entries: v at the selected indices
+    // cache update (all null/0 -> none)
+    uint32_t* c_bits;
+    uint32_t* c_stamp;
+    uint32_t* c_meta;
+    int capacity;
+    int policy;
+    // counters the following GEMV launch expects to be zero
+    uint32_t* zero_ptr;
+    int zero_n;
+};
+
+hipError_t launch_select(const SelectParams& p, hipStream_t stream);
+
+struct CacheInitParams {
+    uint32_t* bits;
+    uint32_t* stamp;
+    uint32_t* meta;
+    const uint32_t* initial_bits;
+    int n;
+};
+hipError_t launch_cache_init(const CacheInitParams& p, hipStream_t stream);
+hipError_t launch_zero_u32(uint32_t* p, int n, hipStream_t stream);
+
+// ---- gathered GEMV -----------------------------------------------------------------------
+struct GemvShape {
+    int lpr;     // lanes per stored row
+    int waves;   // wavefronts per workgroup
+    int ksplit;  // workgroups per output strip
+    int unroll;  // rows in flight per lane group
+};
+
+struct GemvParams {
+    const void* w;            // feature-major weights
+    int64_t row_stride;       // bytes
+    int dtype;                // DIP_F32 | DIP_BF16
+    int n_in;                 // stored rows
+    int n_out;                // elements per row actually produced per segment
+    int nseg;                 // 1: plain GEMV;  2: bundled [up ; gate] with SwiGLU epilogue
+    const int32_t* idx;       // k ascending row indices
+    const float* val;         // compact: val[t] multiplies row idx[t];  or
+    const float* x_full;      // full vector: x_full[idx[t]] multiplies row idx[t] (val == null)
+    int k;
+    float* out;               // n_out floats (nseg == 2: the GLU output, n_out = d_ff)
+    float* partial;           // [ksplit][nseg][n_out] when ksplit > 1
+    uint32_t* counters;       // [strips], zero on entry, when ksplit > 1
+};
+
+GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k);
+int gemv_strips(const GemvShape& s, int dtype, int n_out);
+hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream);
+
+extern GemvShape g_gemv_override;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace dip
+
+#endif  // DIP_INTERNAL_H_

@@ -1,0 +1,270 @@
+"""ctypes binding of libdip.so: same names as the C ABI (include/dip.h), torch tensors in.
+
+PyTorch is used for device memory and streams only.  Tensors must live on the GPU, be
+contiguous and have the dtype the C signature states; the binding passes their data
+pointers through unchanged.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(HERE, "lib", "libdip.so")
+
+DIP_OK, DIP_ERR_INVALID_ARG, DIP_ERR_UNSUPPORTED, DIP_ERR_WORKSPACE, DIP_ERR_HIP = range(5)
+DIP_F32, DIP_BF16, DIP_INT4_G128 = 0, 1, 2
+DIP_LRU, DIP_LFU = 0, 1
+DIP_MAX_N = 32768
+DIP_CACHE_META_WORDS = 8
+META = {"step": 0, "resident": 1, "hits": 2, "inserted": 3, "evicted": 4, "bypassed": 5,
+        "cum_hits": 6, "cum_lookups": 7}
+
+
+class DipError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"libdip status {status}: {msg}")
+        self.status = status
+
+
+class _Weight(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("scales", C.c_void_p), ("dtype", C.c_int32),
+                ("n_in", C.c_int32), ("n_out", C.c_int32), ("reserved", C.c_int32),
+                ("row_stride_bytes", C.c_int64)]
+
+
+class _Mlp(C.Structure):
+    _fields_ = [("w_ug", _Weight), ("w_d", _Weight)]
+
+
+class _Cache(C.Structure):
+    _fields_ = [("bits", C.c_void_p), ("stamp", C.c_void_p), ("meta", C.c_void_p),
+                ("n", C.c_int32), ("capacity", C.c_int32), ("policy", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class _Debug(C.Structure):
+    _fields_ = [("s_in", C.c_void_p), ("mask_in", C.c_void_p), ("idx_in", C.c_void_p),
+                ("h", C.c_void_p), ("s_mid", C.c_void_p), ("mask_mid", C.c_void_p),
+                ("idx_mid", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(lib_path):
+        raise ImportError(
+            f"{lib_path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+            "or python paper_2412_01380_amd/build.py). There is no fallback path.")
+    L = C.CDLL(lib_path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    L.dip_version.restype = i32
+    L.dip_version.argtypes = []
+    L.dip_last_error.restype = C.c_char_p
+    L.dip_last_error.argtypes = []
+    L.dip_ca_scores.restype = i32
+    L.dip_ca_scores.argtypes = [vp, i32, vp, f32, vp, vp]
+    L.dip_prune_topk.restype = i32
+    L.dip_prune_topk.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.dip_cache_init.restype = i32
+    L.dip_cache_init.argtypes = [C.POINTER(_Cache), vp, vp]
+    L.dip_cache_update.restype = i32
+    L.dip_cache_update.argtypes = [C.POINTER(_Cache), vp, vp]
+    L.dip_gathered_gemv_workspace_bytes.restype = sz
+    L.dip_gathered_gemv_workspace_bytes.argtypes = [C.POINTER(_Weight), i32]
+    L.dip_gathered_gemv.restype = i32
+    L.dip_gathered_gemv.argtypes = [C.POINTER(_Weight), vp, vp, i32, vp, vp, sz, vp]
+    L.dip_swiglu_mlp_forward_workspace_bytes.restype = sz
+    L.dip_swiglu_mlp_forward_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32, i32]
+    L.dip_swiglu_mlp_forward.restype = i32
+    L.dip_swiglu_mlp_forward.argtypes = [C.POINTER(_Mlp), vp, i32, i32, C.POINTER(_Cache),
+                                         C.POINTER(_Cache), f32, vp, C.POINTER(_Debug), vp, sz, vp]
+    L.dip_swiglu_mlp_forward_stack.restype = i32
+    L.dip_swiglu_mlp_forward_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, i32, i32,
+                                               C.POINTER(_Cache), C.POINTER(_Cache), f32, vp, i64,
+                                               vp, sz, vp]
+    L.dip_tune_gemv.restype = i32
+    L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
+    return L
+
+
+lib = _load()
+
+EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "dip_cache_init",
+           "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
+           "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
+           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv"]
+
+
+def dip_last_error() -> str:
+    return lib.dip_last_error().decode()
+
+
+def _check(st: int) -> None:
+    if st != DIP_OK:
+        raise DipError(st, dip_last_error())
+
+
+def _ptr(t, dtype=None) -> Optional[int]:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise TypeError("libdip takes device tensors")
+    if not t.is_contiguous():
+        raise TypeError("libdip takes contiguous tensors")
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+class Weight:
+    """A feature-major weight matrix on the device: tensor [n_in][n_out], fp32 or bf16
+    (bf16 may be given as torch.bfloat16, int16 or uint16 holding the bit patterns)."""
+
+    def __init__(self, data):
+        import torch
+        if data.dim() != 2 or not data.is_cuda or data.stride(1) != 1:
+            raise TypeError("weight must be a 2-D device tensor with unit inner stride")
+        if data.dtype == torch.float32:
+            dt = DIP_F32
+        elif data.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+            dt = DIP_BF16
+        else:
+            raise TypeError(f"unsupported weight dtype {data.dtype}")
+        self.tensor = data
+        self.c = _Weight(data.data_ptr(), None, dt, data.shape[0], data.shape[1], 0,
+                         data.stride(0) * data.element_size())
+
+
+class Mlp:
+    """w_ug: bundled up/gate [d_model][2*d_ff]; w_d: down [d_ff][d_model] (feature-major)."""
+
+    def __init__(self, w_ug: Weight, w_d: Weight):
+        self.w_ug, self.w_d = w_ug, w_d
+        self.c = _Mlp(w_ug.c, w_d.c)
+        self.d_model = w_ug.c.n_in
+        self.d_ff = w_d.c.n_in
+
+
+class Cache:
+    """Residency state of one layer's columns, held in caller-owned device tensors."""
+
+    def __init__(self, n: int, capacity: int, policy: int = DIP_LRU, device="cuda"):
+        import torch
+        self.n, self.capacity, self.policy = n, capacity, policy
+        self.bits = torch.zeros((n + 31) // 32, dtype=torch.int32, device=device)
+        self.stamp = torch.zeros(n, dtype=torch.int32, device=device)
+        self.meta = torch.zeros(DIP_CACHE_META_WORDS, dtype=torch.int32, device=device)
+        self.c = _Cache(self.bits.data_ptr(), self.stamp.data_ptr(), self.meta.data_ptr(), n,
+                        capacity, policy, 0)
+
+    def meta_host(self) -> dict:
+        m = self.meta.cpu().numpy().view("uint32")
+        return {k: int(m[i]) for k, i in META.items()}
+
+
+class Debug:
+    """Stage outputs of one forward call (device tensors allocated by the caller)."""
+
+    def __init__(self, d_model: int, d_ff: int, k_in: int, k_mid: int, device="cuda"):
+        import torch
+        self.s_in = torch.empty(d_model, dtype=torch.float32, device=device)
+        self.mask_in = torch.empty((d_model + 31) // 32, dtype=torch.int32, device=device)
+        self.idx_in = torch.empty(k_in, dtype=torch.int32, device=device)
+        self.h = torch.empty(d_ff, dtype=torch.float32, device=device)
+        self.s_mid = torch.empty(d_ff, dtype=torch.float32, device=device)
+        self.mask_mid = torch.empty((d_ff + 31) // 32, dtype=torch.int32, device=device)
+        self.idx_mid = torch.empty(k_mid, dtype=torch.int32, device=device)
+        self.c = _Debug(self.s_in.data_ptr(), self.mask_in.data_ptr(), self.idx_in.data_ptr(),
+                        self.h.data_ptr(), self.s_mid.data_ptr(), self.mask_mid.data_ptr(),
+                        self.idx_mid.data_ptr())
+
+
+def dip_version() -> int:
+    return lib.dip_version()
+
+
+def dip_ca_scores(x, n: int, cache_bits, gamma: float, s_out, stream=None) -> None:
+    import torch
+    _check(lib.dip_ca_scores(_ptr(x, torch.float32), n, _ptr(cache_bits, torch.int32), gamma,
+                             _ptr(s_out, torch.float32), _stream(stream)))
+
+
+def dip_prune_topk(s, n: int, k: int, mask_out, idx_out, stream=None) -> None:
+    import torch
+    _check(lib.dip_prune_topk(_ptr(s, torch.float32), n, k, _ptr(mask_out, torch.int32),
+                              _ptr(idx_out, torch.int32), _stream(stream)))
+
+
+def dip_cache_init(cache: Cache, initial_bits=None, stream=None) -> None:
+    import torch
+    _check(lib.dip_cache_init(C.byref(cache.c), _ptr(initial_bits, torch.int32), _stream(stream)))
+
+
+def dip_cache_update(cache: Cache, mask_bits, stream=None) -> None:
+    import torch
+    _check(lib.dip_cache_update(C.byref(cache.c), _ptr(mask_bits, torch.int32), _stream(stream)))
+
+
+def dip_gathered_gemv_workspace_bytes(w: Weight, k: int) -> int:
+    return lib.dip_gathered_gemv_workspace_bytes(C.byref(w.c), k)
+
+
+def dip_gathered_gemv(w: Weight, x, idx, k: int, y_out, ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_gathered_gemv(C.byref(w.c), _ptr(x, torch.float32), _ptr(idx, torch.int32), k,
+                                 _ptr(y_out, torch.float32), _ptr(ws), ws.numel() * ws.element_size(),
+                                 _stream(stream)))
+
+
+def dip_swiglu_mlp_forward_workspace_bytes(mlp: Mlp, k_in: int, k_mid: int) -> int:
+    return lib.dip_swiglu_mlp_forward_workspace_bytes(C.byref(mlp.c), k_in, k_mid)
+
+
+def dip_swiglu_mlp_forward(mlp: Mlp, x, k_in: int, k_mid: int, cache_in: Optional[Cache],
+                           cache_mid: Optional[Cache], gamma: float, y_out, dbg: Optional[Debug],
+                           ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_swiglu_mlp_forward(
+        C.byref(mlp.c), _ptr(x, torch.float32), k_in, k_mid,
+        C.byref(cache_in.c) if cache_in is not None else None,
+        C.byref(cache_mid.c) if cache_mid is not None else None,
+        gamma, _ptr(y_out, torch.float32), C.byref(dbg.c) if dbg is not None else None,
+        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+class MlpStack:
+    """Host arrays of descriptors for dip_swiglu_mlp_forward_stack (built once, reused)."""
+
+    def __init__(self, mlps: Sequence[Mlp], caches_in: Optional[Sequence[Cache]] = None,
+                 caches_mid: Optional[Sequence[Cache]] = None):
+        n = len(mlps)
+        self.n = n
+        self.mlps = (_Mlp * n)(*[m.c for m in mlps])
+        self.cin = (_Cache * n)(*[c.c for c in caches_in]) if caches_in else None
+        self.cmid = (_Cache * n)(*[c.c for c in caches_mid]) if caches_mid else None
+        self._keep = (list(mlps), caches_in, caches_mid)
+
+
+def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in: int, k_mid: int,
+                                 gamma: float, y_out, y_stride: int, ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_swiglu_mlp_forward_stack(
+        stack.mlps, stack.n, _ptr(x, torch.float32), x_stride, k_in, k_mid, stack.cin, stack.cmid,
+        gamma, _ptr(y_out, torch.float32), y_stride, _ptr(ws), ws.numel() * ws.element_size(),
+        _stream(stream)))
+
+
+def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:
+    _check(lib.dip_tune_gemv(lanes_per_row, waves, ksplit, unroll))
