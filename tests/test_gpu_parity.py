@@ -56,7 +56,7 @@ def test_scores_zero_vector_and_tiny_quotients(D):
     D.dip_ca_scores(dev_f32(np.zeros(n)), n, dev_u32(bits_from_bool(c)), 0.2, s)
     assert not s.cpu().numpy().any()
     # quotients that land in the denormal range must be kept, not flushed
-    x = np.full(n, 1e-30, dtype=np.float32)
+    x = np.full(n, 1e-20, dtype=np.float32)
     x[0] = 1e20
     c[:] = False
     D.dip_ca_scores(dev_f32(x), n, dev_u32(bits_from_bool(c)), 0.2, s)
