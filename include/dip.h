@@ -229,6 +229,23 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
  */
 int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by a pair of HIP events bound to that dispatch (its own begin/end timestamps,
+ * no extra work on the stream), up to max_launches launches; later launches are not timed.
+ * The events are host objects; no device memory is allocated.  dip_profile_read() waits
+ * for the recorded events and returns the summed duration and the number of launches of
+ * one kernel kind.  Process-wide and not thread-safe: meant for a single benchmarking
+ * thread.
+ */
+#define DIP_KERNEL_SELECT_IN 0   /* scores + top-K + cache update at pruning point 1       */
+#define DIP_KERNEL_GEMV_UPGATE 1 /* gathered up/gate GEMV + SwiGLU                          */
+#define DIP_KERNEL_SELECT_MID 2  /* scores + top-K + cache update at pruning point 2       */
+#define DIP_KERNEL_GEMV_DOWN 3   /* gathered down GEMV (also dip_gathered_gemv)             */
+int32_t dip_profile_enable(int32_t max_launches);
+int32_t dip_profile_read(int32_t kind, double* total_ms /* host */, int32_t* launches /* host */);
+int32_t dip_profile_disable(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "dip_internal.h"
 
@@ -23,6 +24,25 @@ int32_t fail(int32_t status, const char* fmt, ...) {
 int32_t check_hip(hipError_t e, const char* what) {
     if (e == hipSuccess) return DIP_OK;
     return fail(DIP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---- per-launch timing pool ---------------------------------------------------------------
+namespace {
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> kind;
+    size_t used = 0;
+} g_prof;
+}  // namespace
+
+bool prof_next(int kind, hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_prof.on || g_prof.used >= g_prof.start.size()) return false;
+    *start = g_prof.start[g_prof.used];
+    *stop = g_prof.stop[g_prof.used];
+    g_prof.kind[g_prof.used] = kind;
+    ++g_prof.used;
+    return true;
 }
 
 namespace {
@@ -139,7 +159,7 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
         s1.capacity = cin->capacity; s1.policy = cin->policy;
     }
     s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
-    int32_t st = check_hip(launch_select(s1, stream), "select (point 1)");
+    int32_t st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
     if (st) return st;
 
     // gathered up/gate GEMV + SwiGLU
@@ -148,7 +168,7 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes; g1.dtype = mlp->w_ug.dtype;
     g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.idx = idx1; g1.val = val1; g1.k = k_in; g1.out = h;
     g1.partial = part_ug; g1.counters = cnt_ug;
-    st = check_hip(launch_gemv(g1, pl.ug, stream), "gathered GEMV (up/gate)");
+    st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
     if (st) return st;
 
     // point 2
@@ -162,7 +182,7 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
         s2.score_bits = cmid->bits; s2.c_bits = cmid->bits; s2.c_stamp = cmid->stamp; s2.c_meta = cmid->meta;
         s2.capacity = cmid->capacity; s2.policy = cmid->policy;
     }
-    st = check_hip(launch_select(s2, stream), "select (point 2)");
+    st = check_hip(launch_select(s2, stream, DIP_KERNEL_SELECT_MID), "select (point 2)");
     if (st) return st;
 
     // gathered down GEMV
@@ -171,7 +191,7 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes; g2.dtype = mlp->w_d.dtype;
     g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.idx = idx2; g2.val = val2; g2.k = k_mid; g2.out = y;
     g2.partial = part_dn; g2.counters = cnt_dn;
-    return check_hip(launch_gemv(g2, pl.dn, stream), "gathered GEMV (down)");
+    return check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
 }
 
 }  // namespace
@@ -198,7 +218,7 @@ int32_t dip_ca_scores(const float* x, int32_t n, const uint32_t* cache_bits, flo
     std::memset(&p, 0, sizeof(p));
     p.v = x; p.n = n; p.k = 1; p.score_bits = cache_bits; p.gamma = gamma;
     p.scores_only = 1; p.s_out = s_out;
-    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_ca_scores");
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream), DIP_KERNEL_SELECT_IN), "dip_ca_scores");
 }
 
 int32_t dip_prune_topk(const float* s, int32_t n, int32_t k, uint32_t* mask_out, int32_t* idx_out,
@@ -211,7 +231,7 @@ int32_t dip_prune_topk(const float* s, int32_t n, int32_t k, uint32_t* mask_out,
     SelectParams p;
     std::memset(&p, 0, sizeof(p));
     p.v = s; p.n = n; p.k = k; p.mask_out = mask_out; p.idx_out = idx_out;
-    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_prune_topk");
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream), DIP_KERNEL_SELECT_IN), "dip_prune_topk");
 }
 
 int32_t dip_cache_init(const dip_cache* cache, const uint32_t* initial_bits, void* stream) {
@@ -232,7 +252,7 @@ int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void
     p.n = cache->n; p.k = 1; p.mask_in = mask_bits;
     p.c_bits = cache->bits; p.c_stamp = cache->stamp; p.c_meta = cache->meta;
     p.capacity = cache->capacity; p.policy = cache->policy;
-    return check_hip(launch_select(p, static_cast<hipStream_t>(stream)), "dip_cache_update");
+    return check_hip(launch_select(p, static_cast<hipStream_t>(stream), DIP_KERNEL_SELECT_IN), "dip_cache_update");
 }
 
 size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k) {
@@ -269,7 +289,7 @@ int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* id
     p.w = w->data; p.row_stride = w->row_stride_bytes; p.dtype = w->dtype; p.n_in = w->n_in; p.n_out = w->n_out;
     p.nseg = 1; p.idx = idx; p.val = nullptr; p.x_full = x; p.k = k; p.out = y_out;
     p.partial = partial; p.counters = counters;
-    return check_hip(launch_gemv(p, s, hs), "dip_gathered_gemv");
+    return check_hip(launch_gemv(p, s, hs, DIP_KERNEL_GEMV_DOWN), "dip_gathered_gemv");
 }
 
 size_t dip_swiglu_mlp_forward_workspace_bytes(const dip_mlp* mlp, int32_t k_in, int32_t k_mid) {
@@ -339,6 +359,55 @@ int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int3
     if (!in(unroll, {0, 1, 2, 4, 8})) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: unroll");
     if (ksplit < 0 || ksplit > 4096) return fail(DIP_ERR_INVALID_ARG, "dip_tune_gemv: ksplit");
     g_gemv_override = GemvShape{lanes_per_row, waves, ksplit, unroll};
+    return DIP_OK;
+}
+
+int32_t dip_profile_disable(void) {
+    for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.kind.clear();
+    g_prof.used = 0;
+    g_prof.on = false;
+    return DIP_OK;
+}
+
+int32_t dip_profile_enable(int32_t max_launches) {
+    if (max_launches < 1 || max_launches > (1 << 20))
+        return fail(DIP_ERR_INVALID_ARG, "dip_profile_enable: max_launches must be in [1, 2^20]");
+    dip_profile_disable();
+    for (int i = 0; i < max_launches; ++i) {
+        hipEvent_t a, b;
+        int32_t st = check_hip(hipEventCreate(&a), "hipEventCreate");
+        if (st) { dip_profile_disable(); return st; }
+        g_prof.start.push_back(a);
+        st = check_hip(hipEventCreate(&b), "hipEventCreate");
+        if (st) { dip_profile_disable(); return st; }
+        g_prof.stop.push_back(b);
+        g_prof.kind.push_back(-1);
+    }
+    g_prof.on = true;
+    return DIP_OK;
+}
+
+int32_t dip_profile_read(int32_t kind, double* total_ms, int32_t* launches) {
+    if (!total_ms || !launches) return fail(DIP_ERR_INVALID_ARG, "dip_profile_read: null output");
+    if (kind < 0 || kind > 3) return fail(DIP_ERR_INVALID_ARG, "dip_profile_read: unknown kernel kind");
+    double sum = 0.0;
+    int32_t n = 0;
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        if (g_prof.kind[i] != kind) continue;
+        int32_t st = check_hip(hipEventSynchronize(g_prof.stop[i]), "hipEventSynchronize");
+        if (st) return st;
+        float ms = 0.f;
+        st = check_hip(hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]), "hipEventElapsedTime");
+        if (st) return st;
+        sum += ms;
+        ++n;
+    }
+    *total_ms = sum;
+    *launches = n;
     return DIP_OK;
 }
 

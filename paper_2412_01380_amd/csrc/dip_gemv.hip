@@ -75,8 +75,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     const bool col_ok = col < p.n_out;
 
     // this workgroup's share of the selected rows
-    const int kb = (int)(((int64_t)p.k * g) / G);
-    const int ke = (int)(((int64_t)p.k * (g + 1)) / G);
+    const int kb = min(p.k, g * p.rows_per_split);
+    const int ke = min(p.k, kb + p.rows_per_split);
 
     float acc[NSEG][EPL];
 #pragma unroll
@@ -86,30 +86,65 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 
     const char* wbase = static_cast<const char*>(p.w) + (size_t)col * sizeof(WT);
     const size_t seg_bytes = (size_t)p.n_out * sizeof(WT);
+    constexpr int ROWS_PER_ITER = UNROLL * ROWS_PER_STEP;
 
-    for (int t0 = kb + wave * RPW + sub; t0 < ke; t0 += UNROLL * ROWS_PER_STEP) {
-        int row[UNROLL];
-        float xv[UNROLL];
+    // (row, multiplier) of one selected feature; rows outside the matrix or past the end of
+    // this workgroup's share come back as row = -1
+    auto fetch = [&](int t, int& row, float& xv) {
+        row = -1;
+        xv = 0.f;
+        if (t < ke) {
+            const int r = p.idx[t];
+            if ((unsigned)r < (unsigned)p.n_in) {
+                row = r;
+                xv = p.val ? p.val[t] : p.x_full[r];
+            }
+        }
+    };
+
+    // Full iterations: every lane group has UNROLL rows, so the weight loads need no
+    // predicates.  The (row, multiplier) pairs of the next iteration are requested right
+    // after this iteration's weight loads, so their latency hides behind the weights.
+    const int n_full = col_ok ? (ke - kb) / ROWS_PER_ITER : 0;
+    int t0 = kb + wave * RPW + sub;
+    int row[UNROLL];
+    float xv[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) fetch(t0 + u * ROWS_PER_STEP, row[u], xv[u]);
+    for (int it = 0; it < n_full; ++it) {
         u32x4 q[UNROLL][NSEG];
+        float xc[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int t = t0 + u * ROWS_PER_STEP;
-            const bool ok = t < ke;
-            row[u] = ok ? p.idx[t] : -1;
-            if ((unsigned)row[u] >= (unsigned)p.n_in) row[u] = -1;  // an index outside the matrix contributes nothing
+            // an index outside the matrix reads row 0 with multiplier 0
+            const size_t off = (size_t)(row[u] < 0 ? 0 : row[u]) * (size_t)p.row_stride;
+            xc[u] = xv[u];
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) q[u][s] = load16(wbase + off + s * seg_bytes);
         }
+        t0 += ROWS_PER_ITER;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) fetch(t0 + u * ROWS_PER_STEP, row[u], xv[u]);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int t = t0 + u * ROWS_PER_STEP;
-            xv[u] = 0.f;
-            if (row[u] >= 0) xv[u] = p.val ? p.val[t] : p.x_full[row[u]];
+#pragma unroll
+            for (int s = 0; s < NSEG; ++s) {
+                float f[EPL];
+                Elem<WT>::widen(q[u][s], f);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], xc[u], acc[s][e]);
+            }
         }
+    }
+    // Tail: fewer than ROWS_PER_ITER rows are left; lane groups without a row skip the load.
+    if (col_ok) {
+        u32x4 q[UNROLL][NSEG];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
                 q[u][s] = u32x4{0u, 0u, 0u, 0u};
-                if (row[u] >= 0 && col_ok)
+                if (row[u] >= 0)
                     q[u][s] = load16(wbase + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
             }
         }
@@ -154,19 +189,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     }
 
     if (G > 1) {
-        // workgroups of one strip
+        // Workgroups of one strip.  Partial sums travel through agent-scope atomics, which
+        // are written through to (and read from) the memory side where all eight L2s agree,
+        // so no L2 write-back or invalidate is needed: waiting for the stores to be
+        // acknowledged (vmcnt = 0) before this workgroup's ticket is taken orders them
+        // before any read by the workgroup that draws the last ticket.
         float* part = p.partial + ((size_t)g * NSEG + oseg) * (size_t)p.n_out + gcol;
         if (owner) __hip_atomic_store(part, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-            const uint32_t prev = __hip_atomic_fetch_add(&p.counters[strip], 1u, __ATOMIC_ACQ_REL,
+            const uint32_t prev = __hip_atomic_fetch_add(&p.counters[strip], 1u, __ATOMIC_RELAXED,
                                                          __HIP_MEMORY_SCOPE_AGENT);
             s_last = (prev == (uint32_t)(G - 1));
         }
         __syncthreads();
         if (!s_last) return;
-        __threadfence();
         sum = 0.f;
         if (owner) {
             for (int gg = 0; gg < G; ++gg) {
@@ -188,55 +226,54 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 }
 
 template <typename WT, int LPR, int WAVES, int UNROLL>
-hipError_t launch_nseg(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+hipError_t launch_nseg(const GemvParams& p, const GemvShape& s, hipStream_t stream, int pk) {
     constexpr int SC = LPR * Elem<WT>::kPerLoad;
     const int strips = (p.n_out + SC - 1) / SC;
     dim3 grid(strips, s.ksplit), block(WAVES * 64);
     if (p.nseg == 2) {
         if constexpr (2 * SC <= WAVES * 64) {
-            hipLaunchKernelGGL((gemv_kernel<WT, LPR, WAVES, UNROLL, 2>), grid, block, 0, stream, p);
+            return launch_timed(gemv_kernel<WT, LPR, WAVES, UNROLL, 2>, grid, block, stream, pk, p);
         } else {
             return hipErrorInvalidConfiguration;
         }
     } else {
         if constexpr (SC <= WAVES * 64) {
-            hipLaunchKernelGGL((gemv_kernel<WT, LPR, WAVES, UNROLL, 1>), grid, block, 0, stream, p);
+            return launch_timed(gemv_kernel<WT, LPR, WAVES, UNROLL, 1>, grid, block, stream, pk, p);
         } else {
             return hipErrorInvalidConfiguration;
         }
     }
-    return hipGetLastError();
 }
 
 template <typename WT, int LPR, int WAVES>
-hipError_t launch_unroll(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+hipError_t launch_unroll(const GemvParams& p, const GemvShape& s, hipStream_t stream, int pk) {
     switch (s.unroll) {
-        case 1: return launch_nseg<WT, LPR, WAVES, 1>(p, s, stream);
-        case 2: return launch_nseg<WT, LPR, WAVES, 2>(p, s, stream);
-        case 4: return launch_nseg<WT, LPR, WAVES, 4>(p, s, stream);
-        case 8: return launch_nseg<WT, LPR, WAVES, 8>(p, s, stream);
+        case 1: return launch_nseg<WT, LPR, WAVES, 1>(p, s, stream, pk);
+        case 2: return launch_nseg<WT, LPR, WAVES, 2>(p, s, stream, pk);
+        case 4: return launch_nseg<WT, LPR, WAVES, 4>(p, s, stream, pk);
+        case 8: return launch_nseg<WT, LPR, WAVES, 8>(p, s, stream, pk);
     }
     return hipErrorInvalidConfiguration;
 }
 
 template <typename WT, int LPR>
-hipError_t launch_waves(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+hipError_t launch_waves(const GemvParams& p, const GemvShape& s, hipStream_t stream, int pk) {
     switch (s.waves) {
-        case 2: return launch_unroll<WT, LPR, 2>(p, s, stream);
-        case 4: return launch_unroll<WT, LPR, 4>(p, s, stream);
-        case 8: return launch_unroll<WT, LPR, 8>(p, s, stream);
-        case 16: return launch_unroll<WT, LPR, 16>(p, s, stream);
+        case 2: return launch_unroll<WT, LPR, 2>(p, s, stream, pk);
+        case 4: return launch_unroll<WT, LPR, 4>(p, s, stream, pk);
+        case 8: return launch_unroll<WT, LPR, 8>(p, s, stream, pk);
+        case 16: return launch_unroll<WT, LPR, 16>(p, s, stream, pk);
     }
     return hipErrorInvalidConfiguration;
 }
 
 template <typename WT>
-hipError_t launch_lpr(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
+hipError_t launch_lpr(const GemvParams& p, const GemvShape& s, hipStream_t stream, int pk) {
     switch (s.lpr) {
-        case 8: return launch_waves<WT, 8>(p, s, stream);
-        case 16: return launch_waves<WT, 16>(p, s, stream);
-        case 32: return launch_waves<WT, 32>(p, s, stream);
-        case 64: return launch_waves<WT, 64>(p, s, stream);
+        case 8: return launch_waves<WT, 8>(p, s, stream, pk);
+        case 16: return launch_waves<WT, 16>(p, s, stream, pk);
+        case 32: return launch_waves<WT, 32>(p, s, stream, pk);
+        case 64: return launch_waves<WT, 64>(p, s, stream, pk);
     }
     return hipErrorInvalidConfiguration;
 }
@@ -274,9 +311,11 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     return s;
 }
 
-hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream) {
-    if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream);
-    if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream);
+hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t stream, int pk) {
+    GemvParams p = p0;
+    p.rows_per_split = (p.k + s.ksplit - 1) / s.ksplit;
+    if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream, pk);
+    if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
     return hipErrorInvalidValue;
 }
 

@@ -3,6 +3,7 @@
 #define DIP_INTERNAL_H_
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "dip.h"
@@ -12,6 +13,24 @@ namespace dip {
 // ---- error reporting -------------------------------------------------------------------
 int32_t fail(int32_t status, const char* fmt, ...);
 int32_t check_hip(hipError_t e, const char* what);
+
+// ---- optional per-launch timing ---------------------------------------------------------
+// Hands out the next (start, stop) event pair for a launch of `kind`, or false when timing
+// is off or the pool is used up.
+bool prof_next(int kind, hipEvent_t* start, hipEvent_t* stop);
+
+// Launch `kernel`, with timing events bound to the dispatch when the profiler provides them.
+template <typename K, typename P>
+inline hipError_t launch_timed(K kernel, dim3 grid, dim3 block, hipStream_t stream, int prof_kind,
+                               const P& params) {
+    hipEvent_t e0, e1;
+    if (prof_kind >= 0 && prof_next(prof_kind, &e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, e0, e1, 0, params);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, params);
+    }
+    return hipGetLastError();
+}
 
 // ---- selection kernel (scores -> top-K -> cache update), one workgroup ------------------
 constexpr int kSelThreads = 1024;
@@ -39,7 +58,7 @@ struct SelectParams {
     int zero_n;
 };
 
-hipError_t launch_select(const SelectParams& p, hipStream_t stream);
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind);
 
 struct CacheInitParams {
     uint32_t* bits;
@@ -70,6 +89,7 @@ struct GemvParams {
     const float* val;         // compact: val[t] multiplies row idx[t];  or
     const float* x_full;      // full vector: x_full[idx[t]] multiplies row idx[t] (val == null)
     int k;
+    int rows_per_split;       // ceil(k / ksplit), filled in by launch_gemv
     float* out;               // n_out floats (nseg == 2: the GLU output, n_out = d_ff)
     float* partial;           // [ksplit][nseg][n_out] when ksplit > 1
     uint32_t* counters;       // [strips], zero on entry, when ksplit > 1
@@ -77,7 +97,7 @@ struct GemvParams {
 
 GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k);
 int gemv_strips(const GemvShape& s, int dtype, int n_out);
-hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream);
+hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream, int prof_kind);
 
 extern GemvShape g_gemv_override;
 

@@ -379,25 +379,24 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 }
 
 template <int ITEMS>
-hipError_t launch_items(const SelectParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(1), dim3(kSelThreads), 0, stream, p);
-    return hipGetLastError();
+hipError_t launch_items(const SelectParams& p, hipStream_t stream, int prof_kind) {
+    return launch_timed(select_kernel<ITEMS>, dim3(1), dim3(kSelThreads), stream, prof_kind, p);
 }
 
 }  // namespace
 
-hipError_t launch_select(const SelectParams& p, hipStream_t stream) {
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind) {
     const int items = (p.n + kSelThreads - 1) / kSelThreads;
-    if (items <= 1) return launch_items<1>(p, stream);
-    if (items <= 2) return launch_items<2>(p, stream);
-    if (items <= 4) return launch_items<4>(p, stream);
-    if (items <= 6) return launch_items<6>(p, stream);
-    if (items <= 8) return launch_items<8>(p, stream);
-    if (items <= 12) return launch_items<12>(p, stream);
-    if (items <= 16) return launch_items<16>(p, stream);
-    if (items <= 20) return launch_items<20>(p, stream);
-    if (items <= 24) return launch_items<24>(p, stream);
-    return launch_items<32>(p, stream);
+    if (items <= 1) return launch_items<1>(p, stream, prof_kind);
+    if (items <= 2) return launch_items<2>(p, stream, prof_kind);
+    if (items <= 4) return launch_items<4>(p, stream, prof_kind);
+    if (items <= 6) return launch_items<6>(p, stream, prof_kind);
+    if (items <= 8) return launch_items<8>(p, stream, prof_kind);
+    if (items <= 12) return launch_items<12>(p, stream, prof_kind);
+    if (items <= 16) return launch_items<16>(p, stream, prof_kind);
+    if (items <= 20) return launch_items<20>(p, stream, prof_kind);
+    if (items <= 24) return launch_items<24>(p, stream, prof_kind);
+    return launch_items<32>(p, stream, prof_kind);
 }
 
 hipError_t launch_cache_init(const CacheInitParams& p, hipStream_t stream) {

@@ -84,6 +84,12 @@ def _load() -> C.CDLL:
                                                vp, sz, vp]
     L.dip_tune_gemv.restype = i32
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
+    L.dip_profile_enable.restype = i32
+    L.dip_profile_enable.argtypes = [i32]
+    L.dip_profile_read.restype = i32
+    L.dip_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    L.dip_profile_disable.restype = i32
+    L.dip_profile_disable.argtypes = []
     return L
 
 
@@ -92,7 +98,8 @@ lib = _load()
 EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "dip_cache_init",
            "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
-           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv"]
+           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv", "dip_profile_enable", "dip_profile_read",
+           "dip_profile_disable"]
 
 
 def dip_last_error() -> str:
@@ -268,3 +275,18 @@ def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in: int, k
 
 def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:
     _check(lib.dip_tune_gemv(lanes_per_row, waves, ksplit, unroll))
+
+
+def dip_profile_enable(max_launches: int) -> None:
+    _check(lib.dip_profile_enable(max_launches))
+
+
+def dip_profile_read(kind: int):
+    """(total milliseconds, launches) of one kernel kind since dip_profile_enable()."""
+    ms, n = C.c_double(0.0), C.c_int32(0)
+    _check(lib.dip_profile_read(kind, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
+
+
+def dip_profile_disable() -> None:
+    _check(lib.dip_profile_disable())
