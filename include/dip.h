@@ -116,11 +116,11 @@ typedef struct dip_cache {
 typedef struct dip_debug {
     float* s_in;        /* d_model scores at pruning point 1                                */
     uint32_t* mask_in;  /* ceil(d_model/32) words                                           */
-    int32_t* idx_in;    /* k_in ascending indices                                           */
+    int32_t* idx_in;    /* k_in ascending indices (16-byte aligned)                         */
     float* h;           /* d_ff: the sparse GLU output  GLU~(x)                             */
     float* s_mid;       /* d_ff scores at pruning point 2                                   */
     uint32_t* mask_mid; /* ceil(d_ff/32) words                                              */
-    int32_t* idx_mid;   /* k_mid ascending indices                                          */
+    int32_t* idx_mid;   /* k_mid ascending indices (16-byte aligned)                        */
 } dip_debug;
 
 /* (major << 16) | minor. */

@@ -309,6 +309,8 @@ static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const floa
         int32_t st = validate_gamma(gamma);
         if (st) return st;
     }
+    if (dbg && (!aligned(dbg->idx_in, 16) || !aligned(dbg->idx_mid, 16)))
+        return fail(DIP_ERR_UNSUPPORTED, "forward: debug index lists must be 16-byte aligned");
     size_t need = 0;
     for (int l = 0; l < n_layers; ++l) {
         int32_t st = validate_mlp(&mlps[l], k_in, k_mid);

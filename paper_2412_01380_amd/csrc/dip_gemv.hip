@@ -63,7 +63,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     constexpr int EPL = Elem<WT>::kPerLoad;
     constexpr int RPW = 64 / LPR;          // rows per wavefront step
     constexpr int SC = LPR * EPL;          // strip columns
-    constexpr int ROWS_PER_STEP = WAVES * RPW;
     __shared__ float red[WAVES][NSEG][SC];
     __shared__ int s_last;
 
@@ -75,7 +74,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     const bool col_ok = col < p.n_out;
 
     // this workgroup's share of the selected rows
-    const int kb = min(p.k, g * p.rows_per_split);
+    const int kb = min(p.k, g * p.rows_per_split);   // rows_per_split is a multiple of 8
     const int ke = min(p.k, kb + p.rows_per_split);
 
     float acc[NSEG][EPL];
@@ -86,45 +85,65 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 
     const char* wbase = static_cast<const char*>(p.w) + (size_t)col * sizeof(WT);
     const size_t seg_bytes = (size_t)p.n_out * sizeof(WT);
-    constexpr int ROWS_PER_ITER = UNROLL * ROWS_PER_STEP;
+    constexpr int NG = WAVES * RPW;            // lane groups per workgroup
+    constexpr int ROWS_PER_ITER = UNROLL * NG;
 
-    // (row, multiplier) of one selected feature; rows outside the matrix or past the end of
-    // this workgroup's share come back as row = -1
-    auto fetch = [&](int t, int& row, float& xv) {
-        row = -1;
-        xv = 0.f;
-        if (t < ke) {
-            const int r = p.idx[t];
-            if ((unsigned)r < (unsigned)p.n_in) {
-                row = r;
-                xv = p.val ? p.val[t] : p.x_full[r];
-            }
-        }
-    };
-
-    // Full iterations: every lane group has UNROLL rows, so the weight loads need no
-    // predicates.  The (row, multiplier) pairs of the next iteration are requested right
-    // after this iteration's weight loads, so their latency hides behind the weights.
+    // Every lane group takes UNROLL consecutive selected rows per iteration, so their
+    // indices and multipliers arrive as one vector load each.  Full iterations need no
+    // predicates; the pairs of the next iteration are requested right after this
+    // iteration's weight loads so that their latency hides behind the weights.
+    const int gid = wave * RPW + sub;
     const int n_full = col_ok ? (ke - kb) / ROWS_PER_ITER : 0;
-    int t0 = kb + wave * RPW + sub;
+    const bool vec_ok = p.val != nullptr;      // compact multipliers, 16-byte aligned lists
+    int t0 = kb + gid * UNROLL;
+
     int row[UNROLL];
     float xv[UNROLL];
+    auto fetch_full = [&](int t) {
+        if (vec_ok) {
+            if constexpr (UNROLL % 4 == 0) {
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) fetch(t0 + u * ROWS_PER_STEP, row[u], xv[u]);
+                for (int u = 0; u < UNROLL; u += 4) {
+                    const int4 r4 = *reinterpret_cast<const int4*>(p.idx + t + u);
+                    const float4 x4 = *reinterpret_cast<const float4*>(p.val + t + u);
+                    row[u] = r4.x; row[u + 1] = r4.y; row[u + 2] = r4.z; row[u + 3] = r4.w;
+                    xv[u] = x4.x; xv[u + 1] = x4.y; xv[u + 2] = x4.z; xv[u + 3] = x4.w;
+                }
+            } else if constexpr (UNROLL == 2) {
+                const int2 r2 = *reinterpret_cast<const int2*>(p.idx + t);
+                const float2 x2 = *reinterpret_cast<const float2*>(p.val + t);
+                row[0] = r2.x; row[1] = r2.y;
+                xv[0] = x2.x; xv[1] = x2.y;
+            } else {
+                row[0] = p.idx[t];
+                xv[0] = p.val[t];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) row[u] = p.idx[t + u];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+                xv[u] = (unsigned)row[u] < (unsigned)p.n_in ? p.x_full[row[u]] : 0.f;
+        }
+        // an index outside the matrix reads row 0 with multiplier 0
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if ((unsigned)row[u] >= (unsigned)p.n_in) { row[u] = 0; xv[u] = 0.f; }
+    };
+
+    if (n_full > 0) fetch_full(t0);
     for (int it = 0; it < n_full; ++it) {
         u32x4 q[UNROLL][NSEG];
         float xc[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            // an index outside the matrix reads row 0 with multiplier 0
-            const size_t off = (size_t)(row[u] < 0 ? 0 : row[u]) * (size_t)p.row_stride;
+            const size_t off = (size_t)row[u] * (size_t)p.row_stride;
             xc[u] = xv[u];
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) q[u][s] = load16(wbase + off + s * seg_bytes);
         }
         t0 += ROWS_PER_ITER;
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) fetch(t0 + u * ROWS_PER_STEP, row[u], xv[u]);
+        if (it + 1 < n_full) fetch_full(t0);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
@@ -136,9 +155,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             }
         }
     }
-    // Tail: fewer than ROWS_PER_ITER rows are left; lane groups without a row skip the load.
-    if (col_ok) {
+    // Tail: fewer than ROWS_PER_ITER rows are left; rows past the end are skipped.
+    if (col_ok && t0 < ke) {
         u32x4 q[UNROLL][NSEG];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int t = t0 + u;
+            row[u] = -1;
+            xv[u] = 0.f;
+            if (t < ke) {
+                const int r = p.idx[t];
+                if ((unsigned)r < (unsigned)p.n_in) {
+                    row[u] = r;
+                    xv[u] = p.val ? p.val[t] : p.x_full[r];
+                }
+            }
+        }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
@@ -205,11 +237,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
         }
         __syncthreads();
         if (!s_last) return;
+        // eight partial sums in flight at a time, added in workgroup order
         sum = 0.f;
         if (owner) {
-            for (int gg = 0; gg < G; ++gg) {
-                const float* src = p.partial + ((size_t)gg * NSEG + oseg) * (size_t)p.n_out + gcol;
-                sum += __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float* src0 = p.partial + (size_t)oseg * (size_t)p.n_out + gcol;
+            const size_t gstride = (size_t)NSEG * (size_t)p.n_out;
+            for (int g0 = 0; g0 < G; g0 += 8) {
+                float part8[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int gg = g0 + j < G ? g0 + j : G - 1;
+                    part8[j] = __hip_atomic_load(src0 + (size_t)gg * gstride, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (g0 + j < G) sum += part8[j];
             }
         }
     }
@@ -313,7 +356,7 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
 
 hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t stream, int pk) {
     GemvParams p = p0;
-    p.rows_per_split = (p.k + s.ksplit - 1) / s.ksplit;
+    p.rows_per_split = ((p.k + s.ksplit - 1) / s.ksplit + 7) / 8 * 8;   // keeps vector index loads aligned
     if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream, pk);
     if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
     return hipErrorInvalidValue;

@@ -9,120 +9,357 @@
 // ascending index order, which is what the lowest-index tie rule and the ascending
 // index list need.
 //
-// top-K is a three-pass most-significant-digit radix select (12 + 10 + 10 bits) on the
-// 32-bit key patterns with LDS histograms; non-negative floats order like their bit
-// patterns.  The same routine, on the complement of the stamps, picks eviction victims
-// (smallest (stamp, index) first).
-
+// top-K is a most-significant-digit radix select (12 + 10 + 10 bits) on the 32-bit key
+// patterns; non-negative floats order like their bit patterns.  The first digit is
+// histogrammed from the registers; the keys that fall into the threshold bin (a few per
+// cent of the vector) are then compacted into LDS and the two remaining digits only look
+// at those.  The same routine, on the age (current step - stamp) of the evictable
+// columns, picks eviction victims (smallest (stamp, index) first).
 #include "dip_internal.h"
+
+#ifndef SEL_WRITELANE
+#define SEL_WRITELANE 0
+#endif
+#ifndef SEL_SEGMENTS
+#define SEL_SEGMENTS 0
+#endif
 
 namespace dip {
 namespace {
 
-constexpr int kWaves = kSelThreads / 64;  // 16
+constexpr int kWaves = kSelThreads / 64;            // 16
 constexpr int kMaxItems = DIP_MAX_N / kSelThreads;  // 32
 constexpr int kMaxTiles = kMaxItems * kWaves;       // 512
+constexpr int kCandSeg = 256;                       // threshold-bin keys one wavefront may park in LDS
+constexpr int kCandCap = kCandSeg * kWaves;         // 4096
+constexpr int kBinsA = 4096, kBinsB = 1024, kBinsC = 1024;
+
+constexpr int kVicCap = 12288;   // evictable columns whose (age, index) fit the LDS list
+constexpr int kMaxWords = DIP_MAX_N / 32;  // 1024: one residency / mask word per lane
 
 struct SelShared {
-    uint32_t hist[4096];
+    uint32_t hist[kBinsA + kBinsB + kBinsC];
+    uint32_t cand[kCandCap];
+    uint32_t vkey[kVicCap];          // eviction keys of the evictable columns, ascending index
+    uint16_t vidx[kVicCap];          // ... and their column indices
+    uint32_t cw[kMaxWords];          // residency words (the paper's c)
+    uint32_t mw[kMaxWords];          // mask words (m)
+    uint32_t vpre[kMaxWords];        // evictable columns before each word
     uint32_t tile[2][kMaxTiles];
-    uint32_t wave_tot[kWaves];
+    uint32_t wave_tot[2][kWaves];
     float wave_max[kWaves];
     uint32_t bcast[4];
     uint32_t cnt[8];
+    uint32_t wcnt[kWaves];  // threshold-bin keys found by each wavefront
 };
 
-__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared& sh) {
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel primitives:
+// shifts inside each row of 16 lanes, then the last lane of row 0/2 is added to row 1/3,
+// then lane 31 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+    int v = (int)x;
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
+    return (uint32_t)v;
+}
+
+// Exclusive prefix sum over the 1024 lanes of the workgroup (one barrier).  `phase`
+// alternates between two LDS buffers so that back-to-back calls need no trailing barrier.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelShared& sh, int& phase) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        uint32_t t = __shfl_up(inc, off);
-        if (lane >= off) inc += t;
-    }
-    if (lane == 63) sh.wave_tot[wave] = inc;
+    const uint32_t inc = wave_incl_scan(v);
+    uint32_t* tot = sh.wave_tot[phase];
+    phase ^= 1;
+    if (lane == 63) tot[wave] = inc;
     __syncthreads();
     uint32_t base = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        uint32_t t = sh.wave_tot[w];
+        const uint32_t t = tot[w];
         if (w < wave) base += t;
     }
-    __syncthreads();
     return base + inc - v;
 }
 
-// Add one count per active lane to hist[d].  The lanes that share the first active lane's
-// digit are merged into a single LDS atomic (keeps tie storms and narrow exponent ranges
-// from serialising on one bin); the others add individually.
-__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t d, bool act, int lane) {
-    const uint64_t am = __ballot(act);
-    if (am == 0) return;
-    const int leader = __ffsll((long long)am) - 1;
-    const uint32_t d0 = __shfl(d, leader);
-    const uint64_t same = __ballot(act && d == d0);
-    if (lane == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-    if (act && d != d0) atomicAdd(&hist[d], 1u);
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+    // number of set bits of `mask` at positions below the calling lane
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Among the participating items (bit j of `part` set) find T = the k-th largest key and
-// need = how many keys equal to T belong to the k largest.  Requires 1 <= k <= participants.
-template <int ITEMS>
-__device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS], uint32_t part,
-                                                     uint32_t k, SelShared& sh, uint32_t& T,
+// One count per lane into hist[d]; all 64 lanes of the wavefront must call.  When they all
+// carry the same digit -- tie storms, the high digits of stamps -- lane 0 adds 64 at once
+// instead of 64 serialised LDS atomics.  SKIP_ZERO leaves out lanes whose key is 0 (used
+// where most lanes hold a non-participating column).
+template <bool SKIP_ZERO>
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t d, uint32_t key, int lane) {
+    if (SKIP_ZERO) {
+        if (key != 0u) atomicAdd(&hist[d], 1u);
+    } else {
+        const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+        if (__ballot(d != d0) == 0ull) {      // wave-uniform branch
+            if (lane == 0) atomicAdd(&hist[d0], 64u);
+        } else {
+            atomicAdd(&hist[d], 1u);
+        }
+    }
+}
+
+// Scan the bins from the top: find the bin in which the running count reaches `want`.
+// Returns the bin, the count in the bins above it, and the count inside it.  Ends with a
+// barrier, so every lane holds the same answer and the histogram may be reused.
+template <int PER>
+__device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t want, SelShared& sh,
+                                         int& phase, uint32_t& bin, uint32_t& above,
+                                         uint32_t& inbin) {
+    constexpr int nb = PER * kSelThreads;
+    const int top = nb - 1 - (int)threadIdx.x * PER;  // this lane owns bins top, top-1, ...
+    uint32_t c[PER];
+    uint32_t local = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        c[q] = hist[top - q];
+        local += c[q];
+    }
+    const uint32_t ab = block_excl_scan(local, sh, phase);
+    if (ab < want && want <= ab + local) {
+        uint32_t acc = ab;
+        bool done = false;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            if (!done && want <= acc + c[q]) {
+                sh.bcast[0] = (uint32_t)(top - q);
+                sh.bcast[1] = acc;
+                sh.bcast[2] = c[q];
+                done = true;
+            }
+            acc += c[q];
+        }
+    }
+    __syncthreads();
+    bin = sh.bcast[0];
+    above = sh.bcast[1];
+    inbin = sh.bcast[2];
+}
+
+// Find T = the k-th largest of all ITEMS*1024 keys held by the workgroup and need = how
+// many keys equal to T belong to the k largest.  Keys that must not take part are 0 and
+// the caller guarantees that at least k keys are larger than 0 or that zero keys at the
+// highest indices are harmless (padding).  Requires k >= 1.
+template <int ITEMS, bool SKIP_ZERO>
+__device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS], uint32_t k,
+                                                     SelShared& sh, int& phase, uint32_t& T,
                                                      uint32_t& need) {
     const int tid = threadIdx.x, lane = tid & 63;
-    uint32_t prefix = 0, pmask = 0, remaining = k;
-#pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-        const int nb = pass == 0 ? 4096 : 1024;
-        for (int b = tid; b < nb; b += kSelThreads) sh.hist[b] = 0;
-        __syncthreads();
+    uint32_t* histA = sh.hist;
+    uint32_t* histB = sh.hist + kBinsA;
+    uint32_t* histC = sh.hist + kBinsA + kBinsB;
+    for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) sh.hist[b] = 0u;
+    __syncthreads();
+
+    // digit 1: bits 31..20, every key
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const bool act = ((part >> j) & 1u) && ((key[j] & pmask) == prefix);
-            const uint32_t d = (key[j] >> shift) & (uint32_t)(nb - 1);
-            hist_add(sh.hist, d, act, lane);
+    for (int j = 0; j < ITEMS; ++j) hist_add<SKIP_ZERO>(histA, key[j] >> 20, key[j], lane);
+    __syncthreads();
+    uint32_t b1, above, inbin;
+    find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
+    uint32_t remaining = k - above;
+
+    // Keys of the threshold bin -> LDS, each wavefront into its own segment (their order is
+    // irrelevant for finding the threshold).  A wavefront that finds more than a segment
+    // holds -- tie storms -- sends the remaining digits down the register path instead.
+    const int wave = tid >> 6;
+    uint32_t* seg = sh.cand + wave * kCandSeg;
+    uint32_t wcount = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const bool hit = (key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u);
+        const uint64_t bh = __ballot(hit);
+        if (hit) {
+            const uint32_t off = wcount + lanes_below(bh);
+            if (off < (uint32_t)kCandSeg) seg[off] = key[j];
         }
-        __syncthreads();
-        // lane tid owns `per` bins counted down from the top; bins above it come first
-        const int per = nb / kSelThreads;
-        const int top = nb - 1 - tid * per;
-        uint32_t local = 0;
-        for (int q = 0; q < per; ++q) local += sh.hist[top - q];
-        const uint32_t above = block_excl_scan(local, sh);
-        if (above < remaining && remaining <= above + local) {
-            uint32_t acc = above;
-            int b = top;
-            for (int q = 0; q < per; ++q) {
-                const uint32_t c = sh.hist[top - q];
-                if (remaining <= acc + c) { b = top - q; break; }
-                acc += c;
-            }
-            sh.bcast[0] = (uint32_t)b;
-            sh.bcast[1] = acc;
-        }
-        __syncthreads();
-        const uint32_t b = sh.bcast[0];
-        remaining -= sh.bcast[1];
-        prefix |= b << shift;
-        pmask |= (uint32_t)(nb - 1) << shift;
-        __syncthreads();
+        wcount += (uint32_t)__popcll(bh);
     }
-    T = prefix;
-    need = remaining;
+    if (lane == 0) sh.wcnt[wave] = wcount;
+    __syncthreads();
+    uint32_t wmax = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) wmax = max(wmax, sh.wcnt[w]);
+    const bool compact = SEL_SEGMENTS && wmax <= (uint32_t)kCandSeg;
+
+    // digit 2: bits 19..10
+    if (compact) {
+#pragma unroll
+        for (int q = 0; q < kCandCap / kSelThreads; ++q) {
+            const int slot = q * kSelThreads + tid;       // segment = slot / kCandSeg
+            if ((uint32_t)(slot % kCandSeg) < sh.wcnt[slot / kCandSeg])
+                atomicAdd(&histB[(sh.cand[slot] >> 10) & 1023u], 1u);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u)) {
+                // merge the lanes of a wavefront that share the digit of its first caller
+                const uint32_t d = (key[j] >> 10) & 1023u;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d == d0) {
+                    if (lanes_below(same) == 0u) atomicAdd(&histB[d0], (uint32_t)__popcll(same));
+                } else {
+                    atomicAdd(&histB[d], 1u);
+                }
+            }
+    }
+    __syncthreads();
+    uint32_t b2;
+    find_bin<1>(histB, remaining, sh, phase, b2, above, inbin);
+    remaining -= above;
+    const uint32_t hi = (b1 << 10) | b2;
+
+    // digit 3: bits 9..0
+    if (compact) {
+#pragma unroll
+        for (int q = 0; q < kCandCap / kSelThreads; ++q) {
+            const int slot = q * kSelThreads + tid;
+            if ((uint32_t)(slot % kCandSeg) < sh.wcnt[slot / kCandSeg]) {
+                const uint32_t kk = sh.cand[slot];
+                if ((kk >> 10) == hi) atomicAdd(&histC[kk & 1023u], 1u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 10) == hi && (!SKIP_ZERO || key[j] != 0u)) {
+                const uint32_t d = key[j] & 1023u;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d == d0) {
+                    if (lanes_below(same) == 0u) atomicAdd(&histC[d0], (uint32_t)__popcll(same));
+                } else {
+                    atomicAdd(&histC[d], 1u);
+                }
+            }
+    }
+    __syncthreads();
+    uint32_t b3;
+    find_bin<1>(histC, remaining, sh, phase, b3, above, inbin);
+    T = (hi << 10) | b3;
+    need = remaining - above;
 }
 
-// Exclusive prefix over the (slot, wavefront) tiles of sh.tile[which], in place.
-template <int ITEMS>
-__device__ __forceinline__ void scan_tiles(SelShared& sh, int which) {
-    constexpr int ntiles = ITEMS * kWaves;
+// One count into hist[d] from inside divergent code: when all calling lanes of the
+// wavefront carry the same digit, the first of them adds the whole count.
+__device__ __forceinline__ void hist_add_callers(uint32_t* hist, uint32_t d) {
+    const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+    const uint64_t callers = __ballot(true);
+    const uint64_t same = __ballot(d == d0);
+    if (same == callers) {
+        if (lanes_below(callers) == 0u) atomicAdd(&hist[d0], (uint32_t)__popcll(callers));
+    } else {
+        atomicAdd(&hist[d], 1u);
+    }
+}
+
+// The same selection over a list of `count` keys in LDS; lane `tid` owns the entries
+// [lo, hi).  Requires 1 <= k <= count.
+__device__ __forceinline__ void list_select_largest(const uint32_t* keys, uint32_t lo, uint32_t hi,
+                                                    uint32_t k, SelShared& sh, int& phase,
+                                                    uint32_t& T, uint32_t& need) {
     const int tid = threadIdx.x;
-    const uint32_t mine = tid < ntiles ? sh.tile[which][tid] : 0u;
-    const uint32_t ex = block_excl_scan(mine, sh);
+    uint32_t* histA = sh.hist;
+    uint32_t* histB = sh.hist + kBinsA;
+    uint32_t* histC = sh.hist + kBinsA + kBinsB;
+    for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) sh.hist[b] = 0u;
+    __syncthreads();
+    for (uint32_t e = lo; e < hi; ++e) hist_add_callers(histA, keys[e] >> 20);
+    __syncthreads();
+    uint32_t b1, above, inbin;
+    find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
+    uint32_t remaining = k - above;
+    for (uint32_t e = lo; e < hi; ++e) {
+        const uint32_t kk = keys[e];
+        if ((kk >> 20) == b1) hist_add_callers(histB, (kk >> 10) & 1023u);
+    }
+    __syncthreads();
+    uint32_t b2;
+    find_bin<1>(histB, remaining, sh, phase, b2, above, inbin);
+    remaining -= above;
+    const uint32_t hi2 = (b1 << 10) | b2;
+    for (uint32_t e = lo; e < hi; ++e) {
+        const uint32_t kk = keys[e];
+        if ((kk >> 10) == hi2) hist_add_callers(histC, kk & 1023u);
+    }
+    __syncthreads();
+    uint32_t b3;
+    find_bin<1>(histC, remaining, sh, phase, b3, above, inbin);
+    T = (hi2 << 10) | b3;
+    need = remaining - above;
+}
+
+// Put the wave-uniform value `val` into lane `LANE` of `dst` (one v_writelane).
+template <int LANE>
+__device__ __forceinline__ void write_lane(int& dst, uint32_t val) {
+#if SEL_WRITELANE
+    const int sval = __builtin_amdgcn_readfirstlane((int)val);
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(sval), "n"(LANE));
+#else
+    if ((threadIdx.x & 63) == LANE) dst = (int)val;
+#endif
+}
+
+template <int J, int ITEMS>
+struct TileCount {
+    __device__ static __forceinline__ void eq_gt(const uint32_t (&key)[ITEMS], uint32_t T, int& mine) {
+        const uint32_t ce = (uint32_t)__popcll(__ballot(key[J] == T));
+        const uint32_t cg = (uint32_t)__popcll(__ballot(key[J] > T));
+        write_lane<J>(mine, ce | (cg << 16));
+        if constexpr (J + 1 < ITEMS) TileCount<J + 1, ITEMS>::eq_gt(key, T, mine);
+    }
+    __device__ static __forceinline__ void flag(uint32_t flags, int& mine) {
+        write_lane<J>(mine, (uint32_t)__popcll(__ballot((flags >> J) & 1u)));
+        if constexpr (J + 1 < ITEMS) TileCount<J + 1, ITEMS>::flag(flags, mine);
+    }
+};
+
+// For every (slot, wavefront) tile: how many keys are equal to T (low 16 bits) and larger
+// than T (high 16 bits); then the exclusive prefix of those over the tiles in index order.
+// Lane j of each wavefront returns the prefix of the wavefront's tile in slot j.
+template <int ITEMS>
+__device__ __forceinline__ uint32_t tile_prefix_eq_gt(const uint32_t (&key)[ITEMS], uint32_t T,
+                                                      SelShared& sh, int& phase) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ntiles = ITEMS * kWaves;
+    int mine = 0;
+    TileCount<0, ITEMS>::eq_gt(key, T, mine);
+    static_assert(ITEMS <= 64, "one lane per slot");
+    if (lane < ITEMS) sh.tile[0][lane * kWaves + wave] = (uint32_t)mine;
+    __syncthreads();
+    const uint32_t t = tid < ntiles ? sh.tile[0][tid] : 0u;
+    const uint32_t ex = block_excl_scan(t, sh, phase);
+    if (tid < ntiles) sh.tile[0][tid] = ex;
+    __syncthreads();
+    return lane < ITEMS ? sh.tile[0][lane * kWaves + wave] : 0u;
+}
+
+// Same for a single flag per key (bit j of `flags`): tile counts, prefix, lane j holds slot j.
+template <int ITEMS>
+__device__ __forceinline__ uint32_t tile_prefix_flag(uint32_t flags, int which, SelShared& sh,
+                                                     int& phase) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ntiles = ITEMS * kWaves;
+    int mine = 0;
+    TileCount<0, ITEMS>::flag(flags, mine);
+    if (lane < ITEMS) sh.tile[which][lane * kWaves + wave] = (uint32_t)mine;
+    __syncthreads();
+    const uint32_t t = tid < ntiles ? sh.tile[which][tid] : 0u;
+    const uint32_t ex = block_excl_scan(t, sh, phase);
     if (tid < ntiles) sh.tile[which][tid] = ex;
     __syncthreads();
+    return lane < ITEMS ? sh.tile[which][lane * kWaves + wave] : 0u;
 }
 
 __device__ __forceinline__ void store_ballot_words(uint32_t* words, int nwords, int first_word,
@@ -135,11 +372,13 @@ template <int ITEMS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     __shared__ SelShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint64_t lt = (1ull << lane) - 1ull;
     const int nwords = (p.n + 31) >> 5;
+    int phase = 0;
 
     for (int i = tid; i < p.zero_n; i += kSelThreads) p.zero_ptr[i] = 0u;
 
+    // Features past n hold value 0 and key 0.  They sit at the highest indices, so the
+    // lowest-index tie rule never picks them while k <= n, and they need no masking.
     float v[ITEMS];
     uint32_t key[ITEMS];
     uint32_t valid = 0, cres = 0, sel = 0;
@@ -153,26 +392,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
             if (p.v) v[j] = p.v[i];
         }
     }
+    // residency and (when given) mask words: one per lane, then bit tests out of LDS
     const uint32_t* rb = p.c_bits ? p.c_bits : p.score_bits;
-    if (rb) {
+    if (rb || p.mask_in) {
+        sh.cw[tid] = (rb && tid < nwords) ? rb[tid] : 0u;
+        sh.mw[tid] = (p.mask_in && tid < nwords) ? p.mask_in[tid] : 0u;
+        __syncthreads();
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * kSelThreads + tid;
-            if ((valid >> j) & 1u) {
-                if ((rb[i >> 5] >> (i & 31)) & 1u) cres |= 1u << j;
-            }
+            const int w = j * (kSelThreads / 32) + (tid >> 5);
+            if ((sh.cw[w] >> (tid & 31)) & 1u) cres |= 1u << j;
+            if ((sh.mw[w] >> (tid & 31)) & 1u) sel |= 1u << j;
         }
+        cres &= valid;
+        sel &= valid;
     }
 
-    if (p.mask_in) {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * kSelThreads + tid;
-            if ((valid >> j) & 1u) {
-                if ((p.mask_in[i >> 5] >> (i & 31)) & 1u) sel |= 1u << j;
-            }
-        }
-    } else {
+    if (!p.mask_in) {
         // ---- Alg. 1 step 1: scores --------------------------------------------------
         if (p.score_bits) {
             float m = 0.f;
@@ -211,128 +447,171 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) key[j] <<= 1;
         uint32_t T, need;
-        block_select_largest<ITEMS>(key, valid, (uint32_t)p.k, sh, T, need);
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const bool ok = (valid >> j) & 1u;
-            const uint64_t be = __ballot(ok && key[j] == T);
-            const uint64_t bg = __ballot(ok && key[j] > T);
-            if (lane == 0) {
-                sh.tile[0][j * kWaves + wave] = (uint32_t)__popcll(be);
-                sh.tile[1][j * kWaves + wave] = (uint32_t)__popcll(bg);
-            }
-        }
-        __syncthreads();
-        scan_tiles<ITEMS>(sh, 0);
-        scan_tiles<ITEMS>(sh, 1);
+        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need);
+        const int pre = (int)tile_prefix_eq_gt<ITEMS>(key, T, sh, phase);
+        const bool want_words = p.mask_out || p.c_bits;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const int i = j * kSelThreads + tid;
-            const bool ok = (valid >> j) & 1u;
-            const bool e = ok && key[j] == T;
-            const bool g = ok && key[j] > T;
-            const uint64_t be = __ballot(e);
-            const uint32_t eq_before = sh.tile[0][j * kWaves + wave];
-            const uint32_t gt_before = sh.tile[1][j * kWaves + wave];
-            const uint32_t rank = eq_before + (uint32_t)__popcll(be & lt);
-            const bool s = g || (e && rank < need);
-            const uint64_t bs = __ballot(s);
-            if (s) {
+            const uint32_t packed = (uint32_t)__builtin_amdgcn_readlane(pre, j);
+            const uint32_t eq_before = packed & 0xffffu, gt_before = packed >> 16;
+            const uint64_t be = __ballot(key[j] == T);
+            bool mine = key[j] > T;
+            if (be) {
+                // ties at the threshold: the `need` lowest indices among them are selected
+                mine = mine || (key[j] == T && eq_before + lanes_below(be) < need);
+            }
+            const uint64_t bs = __ballot(mine);
+            if (mine) {
                 sel |= 1u << j;
-                const uint32_t pos = gt_before + min(eq_before, need) + (uint32_t)__popcll(bs & lt);
+                const uint32_t pos = gt_before + min(eq_before, need) + lanes_below(bs);
                 if (pos < (uint32_t)p.k) {  // always true; keeps a logic slip from writing out of bounds
                     if (p.idx_out) p.idx_out[pos] = i;
                     if (p.val_out) p.val_out[pos] = v[j];
                 }
             }
+            if (want_words) {
+                // a wave ballot over one slot is two words of the mask
+                const int w0 = j * (kSelThreads / 32) + wave * 2;
+                if (lane == 0) sh.mw[w0] = (uint32_t)bs;
+                if (lane == 32) sh.mw[w0 + 1] = (uint32_t)(bs >> 32);
+            }
         }
-    }
-
-    if (p.mask_out) {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const uint64_t bs = __ballot((sel >> j) & 1u);
-            store_ballot_words(p.mask_out, nwords, (j * kSelThreads + wave * 64) >> 5, bs, lane);
-        }
+        if (want_words) __syncthreads();
+        if (p.mask_out && tid < nwords) p.mask_out[tid] = sh.mw[tid];
     }
 
     // ---- Alg. 1 step 3: c' = cache_update(c, m) ------------------------------------------
+    // Works on the 32-column words of c and m, one word per lane: hits, misses and
+    // evictable columns are bit operations, their counts and running sums one packed
+    // workgroup scan.  Only when something must be evicted are the stamps read and the
+    // evictable columns listed (ascending) in LDS for the selection of the oldest.
     if (p.c_bits) {
         const uint32_t t_now = p.c_meta[DIP_META_STEP];
         const uint32_t cum_hits = p.c_meta[DIP_META_CUM_HITS];
         const uint32_t cum_look = p.c_meta[DIP_META_CUM_LOOKUPS];
-        if (tid < 8) sh.cnt[tid] = 0u;
-        __syncthreads();
-        uint32_t w_res = 0, w_hit = 0, w_miss = 0, w_vic = 0;
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const bool r = (cres >> j) & 1u, s = (sel >> j) & 1u;
-            const uint64_t bmiss = __ballot(s && !r);
-            w_res += (uint32_t)__popcll(__ballot(r));
-            w_hit += (uint32_t)__popcll(__ballot(r && s));
-            w_vic += (uint32_t)__popcll(__ballot(r && !s));
-            w_miss += (uint32_t)__popcll(bmiss);
-            if (lane == 0) sh.tile[0][j * kWaves + wave] = (uint32_t)__popcll(bmiss);
-        }
-        if (lane == 0) {
-            atomicAdd(&sh.cnt[0], w_res);
-            atomicAdd(&sh.cnt[1], w_hit);
-            atomicAdd(&sh.cnt[2], w_miss);
-            atomicAdd(&sh.cnt[3], w_vic);
+        // words past nwords are zero; padding bits of the last word are ignored
+        const uint32_t wmask = (tid == nwords - 1 && (p.n & 31)) ? (1u << (p.n & 31)) - 1u : 0xffffffffu;
+        const uint32_t c = sh.cw[tid] & wmask, m = sh.mw[tid] & wmask;
+        const uint32_t hitw = m & c, missw = m & ~c, vicw = c & ~m;
+        const uint32_t n_missw = (uint32_t)__popc(missw);
+        // two 16-bit counts per scan word: every total is at most 32768
+        const uint32_t A = (uint32_t)__popc(c) | ((uint32_t)__popc(hitw) << 16);
+        const uint32_t B = n_missw | ((uint32_t)__popc(vicw) << 16);
+        const uint32_t exA = block_excl_scan(A, sh, phase);
+        const uint32_t exB = block_excl_scan(B, sh, phase);
+        sh.vpre[tid] = exB >> 16;
+        if (tid == kSelThreads - 1) {
+            sh.cnt[0] = exA + A;
+            sh.cnt[1] = exB + B;
         }
         __syncthreads();
-        const uint32_t n_res = sh.cnt[0], n_hit = sh.cnt[1], n_miss = sh.cnt[2], n_vic = sh.cnt[3];
+        const uint32_t n_res = sh.cnt[0] & 0xffffu, n_hit = sh.cnt[0] >> 16;
+        const uint32_t n_miss = sh.cnt[1] & 0xffffu, n_vic = sh.cnt[1] >> 16;
         const uint32_t cap = (uint32_t)p.capacity;
         const uint32_t n_free = cap > n_res ? cap - n_res : 0u;
         const uint32_t n_ins = min(n_miss, n_free + n_vic);
         const uint32_t n_evict = n_ins > n_free ? n_ins - n_free : 0u;
-        scan_tiles<ITEMS>(sh, 0);  // misses before each tile
 
-        // priority of every column; the complement makes "smallest stamp" the largest key
-        uint32_t ek[ITEMS];
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * kSelThreads + tid;
-            ek[j] = ((valid >> j) & 1u) ? ~p.c_stamp[i] : 0u;
+        // the first n_ins misses (ascending index) are inserted
+        const uint32_t miss_before = exB & 0xffffu;
+        const uint32_t take = n_ins > miss_before ? min(n_ins - miss_before, n_missw) : 0u;
+        uint32_t insw = missw;
+        if (take < n_missw) {   // only the word(s) at the boundary
+            insw = 0u;
+            uint32_t mm = missw;
+            for (uint32_t q = 0; q < take; ++q) {
+                const uint32_t low = mm & (0u - mm);
+                insw |= low;
+                mm ^= low;
+            }
         }
-        uint32_t evict = 0;
-        if (n_evict > 0) {
-            const uint32_t vicm = cres & ~sel;
-            uint32_t T2, need2;
-            block_select_largest<ITEMS>(ek, vicm, n_evict, sh, T2, need2);
+
+        const bool need_stamps = n_evict > 0 || p.policy == DIP_LFU;
+        uint32_t stamp_old[ITEMS];
+        if (need_stamps) {
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) {
-                const bool e = ((vicm >> j) & 1u) && ek[j] == T2;
-                const uint64_t be = __ballot(e);
-                if (lane == 0) sh.tile[1][j * kWaves + wave] = (uint32_t)__popcll(be);
+                const int i = j * kSelThreads + tid;
+                stamp_old[j] = ((valid >> j) & 1u) ? p.c_stamp[i] : 0u;
+            }
+        }
+        if (n_evict > 0) {
+            // Eviction key of an evictable column: its age t_now - stamp (LRU: steps since
+            // last use, LFU: how far its use count lags the step counter), moved up so that
+            // the top bit of t_now becomes bit 31.  The oldest / least used has the largest
+            // key; equal keys go by the lowest index.
+            const int age_shift = __clz((int)(t_now | 1u));
+            const uint32_t vicm = cres & ~sel;
+            uint32_t ek[ITEMS];
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const uint32_t age = t_now > stamp_old[j] ? t_now - stamp_old[j] : 1u;
+                ek[j] = ((vicm >> j) & 1u) ? (age << age_shift) : 0u;
+            }
+            if (n_vic <= (uint32_t)kVicCap) {
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j) {
+                    const bool isv = (vicm >> j) & 1u;
+                    const uint64_t bv = __ballot(isv);
+                    if (isv) {
+                        const uint32_t pos = sh.vpre[j * (kSelThreads / 32) + wave * 2] + lanes_below(bv);
+                        if (pos < (uint32_t)kVicCap) {
+                            sh.vkey[pos] = ek[j];
+                            sh.vidx[pos] = (uint16_t)(j * kSelThreads + tid);
+                        }
+                    }
+                }
+                __syncthreads();
+                const uint32_t chunk = (n_vic + kSelThreads - 1) / kSelThreads;
+                const uint32_t lo = min(n_vic, (uint32_t)tid * chunk), hi = min(n_vic, lo + chunk);
+                uint32_t T2, need2;
+                list_select_largest(sh.vkey, lo, hi, n_evict, sh, phase, T2, need2);
+                uint32_t eqc = 0;
+                for (uint32_t e = lo; e < hi; ++e) eqc += sh.vkey[e] == T2 ? 1u : 0u;
+                uint32_t rank = block_excl_scan(eqc, sh, phase);
+                for (uint32_t e = lo; e < hi; ++e) {
+                    const uint32_t kk = sh.vkey[e];
+                    bool ev = kk > T2;
+                    if (kk == T2) ev = rank++ < need2;
+                    if (ev) {
+                        const uint32_t i = sh.vidx[e];
+                        atomicAnd(&sh.cw[i >> 5], ~(1u << (i & 31u)));
+                    }
+                }
+            } else {
+                // more evictable columns than the list holds: select straight from the registers
+                uint32_t T2, need2;
+                block_select_largest<ITEMS, true>(ek, n_evict, sh, phase, T2, need2);
+                const int pre2 = (int)tile_prefix_eq_gt<ITEMS>(ek, T2, sh, phase);
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j) {
+                    const uint32_t i = (uint32_t)(j * kSelThreads + tid);
+                    const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane(pre2, j) & 0xffffu;
+                    const uint64_t be = __ballot(ek[j] == T2);
+                    bool ev = ek[j] > T2;
+                    if (be) ev = ev || (ek[j] == T2 && eq_before + lanes_below(be) < need2);
+                    if (ev) atomicAnd(&sh.cw[i >> 5], ~(1u << (i & 31u)));
+                }
             }
             __syncthreads();
-            scan_tiles<ITEMS>(sh, 1);
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) {
-                const bool vj = (vicm >> j) & 1u;
-                const bool e = vj && ek[j] == T2;
-                const bool g = vj && ek[j] > T2;
-                const uint64_t be = __ballot(e);
-                const uint32_t rank = sh.tile[1][j * kWaves + wave] + (uint32_t)__popcll(be & lt);
-                if (g || (e && rank < need2)) evict |= 1u << j;
-            }
         }
+        const uint32_t newc = (sh.cw[tid] & wmask) | insw;
+        __syncthreads();          // every lane has read its word before any is replaced
+        sh.cw[tid] = newc;
+        if (tid < nwords) p.c_bits[tid] = newc;
+        __syncthreads();
+        // stamps: LRU marks everything used by this token that is resident afterwards
+        // (hits and inserted columns); LFU counts every use
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const int i = j * kSelThreads + tid;
-            const bool r = (cres >> j) & 1u, s = (sel >> j) & 1u;
-            const bool miss = s && !r;
-            const uint64_t bm = __ballot(miss);
-            const uint32_t rank = sh.tile[0][j * kWaves + wave] + (uint32_t)__popcll(bm & lt);
-            const bool ins = miss && rank < n_ins;
-            const bool newc = (r && !((evict >> j) & 1u)) || ins;
-            const uint64_t bn = __ballot(newc);
-            store_ballot_words(p.c_bits, nwords, (j * kSelThreads + wave * 64) >> 5, bn, lane);
-            if (p.policy == DIP_LFU) {
-                if (s) p.c_stamp[i] = ~ek[j] + 1u;
-            } else {
-                if ((r && s) || ins) p.c_stamp[i] = t_now;
+            if ((sel >> j) & 1u) {
+                if (p.policy == DIP_LFU) {
+                    p.c_stamp[i] = stamp_old[j] + 1u;
+                } else if ((sh.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u) {
+                    p.c_stamp[i] = t_now;
+                }
             }
         }
         if (tid == 0) {

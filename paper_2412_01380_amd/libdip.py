@@ -11,7 +11,8 @@ import os
 from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.path.join(HERE, "lib", "libdip.so")
+# DIP_LIBRARY points the binding at another build of the same ABI (e.g. an instrumented one)
+lib_path = os.environ.get("DIP_LIBRARY") or os.path.join(HERE, "lib", "libdip.so")
 
 DIP_OK, DIP_ERR_INVALID_ARG, DIP_ERR_UNSUPPORTED, DIP_ERR_WORKSPACE, DIP_ERR_HIP = range(5)
 DIP_F32, DIP_BF16, DIP_INT4_G128 = 0, 1, 2
