@@ -330,8 +330,12 @@ int gemv_strips(const GemvShape& s, int dtype, int n_out) {
 }
 
 GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
+    // Defaults from launch-shape sweeps on MI355X (Phi-3-Mini, Llama-3-8B and Phi-3-Medium
+    // shaped layers): 16 lanes per row, 8 wavefronts, 4 rows in flight per lane group, and
+    // enough row splits that a workgroup streams a few hundred rows -- long enough to
+    // amortise its prologue and reduction, short enough to fill 256 compute units.
     GemvShape s;
-    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : 8;
+    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : 16;
     s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
     s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
     // a bundled strip needs 2*SC lanes for its epilogue
@@ -340,13 +344,15 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     if (g_gemv_override.ksplit) {
         s.ksplit = g_gemv_override.ksplit;
     } else {
-        // aim for about four workgroups per compute unit
         const int strips = gemv_strips(s, dtype, n_out);
-        int ks = (1024 + strips - 1) / strips;
+        const int rows_per_wg = nseg == 2 ? 384 : 512;
+        int ks = (k + rows_per_wg / 2) / rows_per_wg;
         if (ks < 1) ks = 1;
-        // keep at least one full step of rows per workgroup
-        const int rows_per_step = s.waves * (64 / s.lpr);
-        while (ks > 1 && k / ks < rows_per_step) --ks;
+        const int min_wgs = 192;
+        if (strips * ks < min_wgs) ks = (min_wgs + strips - 1) / strips;
+        // but keep at least one full iteration of rows per workgroup
+        const int rows_per_iter = s.waves * (64 / s.lpr) * s.unroll;
+        while (ks > 1 && k / ks < rows_per_iter) --ks;
         s.ksplit = ks;
     }
     if (s.ksplit > k) s.ksplit = k;

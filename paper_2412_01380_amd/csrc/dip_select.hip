@@ -266,9 +266,10 @@ __device__ __forceinline__ void hist_add_callers(uint32_t* hist, uint32_t d) {
 
 // The same selection over a list of `count` keys in LDS; lane `tid` owns the entries
 // [lo, hi).  Requires 1 <= k <= count.
+// `zero_low` low bits of every key are zero; digits made only of such bits are skipped.
 __device__ __forceinline__ void list_select_largest(const uint32_t* keys, uint32_t lo, uint32_t hi,
-                                                    uint32_t k, SelShared& sh, int& phase,
-                                                    uint32_t& T, uint32_t& need) {
+                                                    uint32_t k, int zero_low, SelShared& sh,
+                                                    int& phase, uint32_t& T, uint32_t& need) {
     const int tid = threadIdx.x;
     uint32_t* histA = sh.hist;
     uint32_t* histB = sh.hist + kBinsA;
@@ -280,6 +281,11 @@ __device__ __forceinline__ void list_select_largest(const uint32_t* keys, uint32
     uint32_t b1, above, inbin;
     find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
     uint32_t remaining = k - above;
+    if (zero_low >= 20) {   // the first digit is the whole key
+        T = b1 << 20;
+        need = remaining;
+        return;
+    }
     for (uint32_t e = lo; e < hi; ++e) {
         const uint32_t kk = keys[e];
         if ((kk >> 20) == b1) hist_add_callers(histB, (kk >> 10) & 1023u);
@@ -289,6 +295,11 @@ __device__ __forceinline__ void list_select_largest(const uint32_t* keys, uint32
     find_bin<1>(histB, remaining, sh, phase, b2, above, inbin);
     remaining -= above;
     const uint32_t hi2 = (b1 << 10) | b2;
+    if (zero_low >= 10) {
+        T = hi2 << 10;
+        need = remaining;
+        return;
+    }
     for (uint32_t e = lo; e < hi; ++e) {
         const uint32_t kk = keys[e];
         if ((kk >> 10) == hi2) hist_add_callers(histC, kk & 1023u);
@@ -566,7 +577,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
                 const uint32_t chunk = (n_vic + kSelThreads - 1) / kSelThreads;
                 const uint32_t lo = min(n_vic, (uint32_t)tid * chunk), hi = min(n_vic, lo + chunk);
                 uint32_t T2, need2;
-                list_select_largest(sh.vkey, lo, hi, n_evict, sh, phase, T2, need2);
+                list_select_largest(sh.vkey, lo, hi, n_evict, age_shift, sh, phase, T2, need2);
                 uint32_t eqc = 0;
                 for (uint32_t e = lo; e < hi; ++e) eqc += sh.vkey[e] == T2 ? 1u : 0u;
                 uint32_t rank = block_excl_scan(eqc, sh, phase);
@@ -666,16 +677,24 @@ hipError_t launch_items(const SelectParams& p, hipStream_t stream, int prof_kind
 
 hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind) {
     const int items = (p.n + kSelThreads - 1) / kSelThreads;
-    if (items <= 1) return launch_items<1>(p, stream, prof_kind);
-    if (items <= 2) return launch_items<2>(p, stream, prof_kind);
-    if (items <= 4) return launch_items<4>(p, stream, prof_kind);
-    if (items <= 6) return launch_items<6>(p, stream, prof_kind);
-    if (items <= 8) return launch_items<8>(p, stream, prof_kind);
-    if (items <= 12) return launch_items<12>(p, stream, prof_kind);
-    if (items <= 16) return launch_items<16>(p, stream, prof_kind);
-    if (items <= 20) return launch_items<20>(p, stream, prof_kind);
-    if (items <= 24) return launch_items<24>(p, stream, prof_kind);
-    return launch_items<32>(p, stream, prof_kind);
+    switch (items) {
+        case 1: return launch_items<1>(p, stream, prof_kind);
+        case 2: return launch_items<2>(p, stream, prof_kind);
+        case 3: return launch_items<3>(p, stream, prof_kind);
+        case 4: return launch_items<4>(p, stream, prof_kind);
+        case 5: return launch_items<5>(p, stream, prof_kind);
+        case 6: return launch_items<6>(p, stream, prof_kind);
+        case 7: case 8: return launch_items<8>(p, stream, prof_kind);
+        case 9: case 10: return launch_items<10>(p, stream, prof_kind);
+        case 11: case 12: return launch_items<12>(p, stream, prof_kind);
+        case 13: case 14: return launch_items<14>(p, stream, prof_kind);
+        case 15: case 16: return launch_items<16>(p, stream, prof_kind);
+        case 17: case 18: return launch_items<18>(p, stream, prof_kind);
+        case 19: case 20: return launch_items<20>(p, stream, prof_kind);
+        case 21: case 22: case 23: case 24: return launch_items<24>(p, stream, prof_kind);
+        case 25: case 26: case 27: case 28: return launch_items<28>(p, stream, prof_kind);
+        default: return launch_items<32>(p, stream, prof_kind);
+    }
 }
 
 hipError_t launch_cache_init(const CacheInitParams& p, hipStream_t stream) {
