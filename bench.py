@@ -35,9 +35,28 @@ def parse():
                     help="distinct weight copies (config 2) or stack depth (configs 3, 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=24)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that a counter "
+                         "pass of rocprofv3 can be scaled against it")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP-event pass (roofline becomes null)")
     return ap.parse_args()
+
+
+def measured_traffic(workload: str, ratio: float, shape) -> "int | None":
+    """HBM bytes per up/gate launch from the committed rocprofv3 counter summaries
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), if one was taken
+    for this workload and launch shape; otherwise None."""
+    import glob
+    want = {"workload": workload, "ratio": f"{ratio:g}", "shape": ",".join(str(v) for v in shape)}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "hbm_traffic_*.txt"))):
+        for line in open(path):
+            if not line.startswith("workload="):
+                continue
+            kv = dict(tok.split("=", 1) for tok in line.split())
+            if all(kv.get(k) == v for k, v in want.items()):
+                return int(kv["gemv_upgate_fetch_bytes"]) + int(kv["gemv_upgate_write_bytes"])
+    return None
 
 
 def main():
@@ -137,6 +156,15 @@ def main():
         "setup_s": t_setup,
     }
 
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read
+        dst = torch.empty_like(src)                                        # 1 GiB written
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = {"read": int(src.numel() * 4), "written": int(dst.numel() * 4)}
+        del src, dst
+
     # ---- per-kernel durations from HIP events bound to the dispatches ---------------------
     if not a.no_kernel_events:
         n_prof = min(passes, max(1, 2048 // L))
@@ -150,10 +178,15 @@ def main():
         out["kernels_us"] = {k: (v[0] / v[1] * 1e3 if v[1] else None) for k, v in prof.items()}
         ug_ms, ug_n = prof["gemv_upgate"]
         dn_ms, dn_n = prof["gemv_down"]
+        shape_ug = D.dip_gemv_launch_shape(mlps[0].w_ug, k_in, bundled=True)
+        shape_dn = D.dip_gemv_launch_shape(mlps[0].w_d, k_mid, bundled=False)
+        out["launch_shapes"] = {"gemv_upgate": list(shape_ug), "gemv_down": list(shape_dn),
+                                "fields": "lanes_per_row, waves, ksplit, unroll"}
         if ug_n:
             ach = ug_bytes / (ug_ms / ug_n * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                               "frac": ach / HBM_PEAK_GBS,
+                               "traffic": measured_traffic(cfg.name, r, shape_ug),
                                "kernel": "gemv_kernel (up/gate + SwiGLU)",
                                "algorithmic_bytes_per_launch": ug_bytes,
                                "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n}

@@ -230,6 +230,14 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
 int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll);
 
 /*
+ * The launch shape the gathered GEMV would use for matrix w and k selected rows, for
+ * reports: shape_out (host, 4 ints) = {lanes_per_row, waves, ksplit, unroll}.
+ * bundled != 0 asks for the up/gate kernel of dip_swiglu_mlp_forward (w = the bundled
+ * matrix, two output halves per workgroup), 0 for the plain kernel.
+ */
+int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
  * bracketed by a pair of HIP events bound to that dispatch (its own begin/end timestamps,
  * no extra work on the stream), up to max_launches launches; later launches are not timed.

@@ -364,6 +364,18 @@ int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int3
     return DIP_OK;
 }
 
+int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out) {
+    int32_t st = validate_weight(w, "dip_gemv_launch_shape");
+    if (st) return st;
+    if (!shape_out) return fail(DIP_ERR_INVALID_ARG, "dip_gemv_launch_shape: null output");
+    if (k < 1 || k > w->n_in) return fail(DIP_ERR_INVALID_ARG, "dip_gemv_launch_shape: k must be in [1, n_in]");
+    if (bundled && (w->n_out % 2)) return fail(DIP_ERR_INVALID_ARG, "dip_gemv_launch_shape: bundled matrix needs an even n_out");
+    const GemvShape s = bundled ? choose_gemv_shape(w->dtype, w->n_out / 2, 2, k)
+                                : choose_gemv_shape(w->dtype, w->n_out, 1, k);
+    shape_out[0] = s.lpr; shape_out[1] = s.waves; shape_out[2] = s.ksplit; shape_out[3] = s.unroll;
+    return DIP_OK;
+}
+
 int32_t dip_profile_disable(void) {
     for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
     for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);

@@ -85,6 +85,8 @@ def _load() -> C.CDLL:
                                                vp, sz, vp]
     L.dip_tune_gemv.restype = i32
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
+    L.dip_gemv_launch_shape.restype = i32
+    L.dip_gemv_launch_shape.argtypes = [C.POINTER(_Weight), i32, i32, C.POINTER(i32)]
     L.dip_profile_enable.restype = i32
     L.dip_profile_enable.argtypes = [i32]
     L.dip_profile_read.restype = i32
@@ -99,7 +101,7 @@ lib = _load()
 EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "dip_cache_init",
            "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
-           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv", "dip_profile_enable", "dip_profile_read",
+           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
            "dip_profile_disable"]
 
 
@@ -276,6 +278,13 @@ def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in: int, k
 
 def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:
     _check(lib.dip_tune_gemv(lanes_per_row, waves, ksplit, unroll))
+
+
+def dip_gemv_launch_shape(w: Weight, k: int, bundled: bool = False):
+    """(lanes_per_row, waves, ksplit, unroll) the library would launch with."""
+    out = (C.c_int32 * 4)()
+    _check(lib.dip_gemv_launch_shape(C.byref(w.c), k, 1 if bundled else 0, out))
+    return tuple(out)
 
 
 def dip_profile_enable(max_launches: int) -> None:
