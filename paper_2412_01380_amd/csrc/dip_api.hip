@@ -49,18 +49,24 @@ namespace {
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-int elem_bytes(int dtype) { return dtype == DIP_F32 ? 4 : 2; }
+int elem_bits(int dtype) { return dtype == DIP_F32 ? 32 : (dtype == DIP_BF16 ? 16 : 4); }
 
 int32_t validate_weight(const dip_weight* w, const char* name) {
     if (!w) return fail(DIP_ERR_INVALID_ARG, "%s: null descriptor", name);
     if (!w->data) return fail(DIP_ERR_INVALID_ARG, "%s: null data pointer", name);
     if (w->n_in < 1 || w->n_out < 1) return fail(DIP_ERR_INVALID_ARG, "%s: n_in and n_out must be >= 1", name);
     if (w->reserved != 0) return fail(DIP_ERR_INVALID_ARG, "%s: reserved must be 0", name);
-    if (w->dtype == DIP_INT4_G128) return fail(DIP_ERR_UNSUPPORTED, "%s: int4 weights are not implemented", name);
-    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16) return fail(DIP_ERR_UNSUPPORTED, "%s: unknown dtype %d", name, w->dtype);
-    const int eb = elem_bytes(w->dtype);
-    if (w->n_out % (16 / eb)) return fail(DIP_ERR_UNSUPPORTED, "%s: n_out must be a multiple of %d", name, 16 / eb);
-    if (w->row_stride_bytes < (int64_t)w->n_out * eb)
+    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16 && w->dtype != DIP_INT4_G128)
+        return fail(DIP_ERR_UNSUPPORTED, "%s: unknown dtype %d", name, w->dtype);
+    const int bits = elem_bits(w->dtype);
+    const int per_load = 128 / bits;
+    if (w->dtype == DIP_INT4_G128) {
+        if (!w->scales) return fail(DIP_ERR_INVALID_ARG, "%s: int4 weights need a scales pointer", name);
+        if (w->n_out % 128) return fail(DIP_ERR_UNSUPPORTED, "%s: int4 rows must be whole groups of 128", name);
+        if (!aligned(w->scales, 2)) return fail(DIP_ERR_UNSUPPORTED, "%s: scales must be 2-byte aligned", name);
+    }
+    if (w->n_out % per_load) return fail(DIP_ERR_UNSUPPORTED, "%s: n_out must be a multiple of %d", name, per_load);
+    if (w->row_stride_bytes < (int64_t)w->n_out * bits / 8)
         return fail(DIP_ERR_INVALID_ARG, "%s: row_stride_bytes smaller than a row", name);
     if (w->row_stride_bytes % 16 || !aligned(w->data, 16))
         return fail(DIP_ERR_UNSUPPORTED, "%s: rows must start on 16-byte boundaries", name);
@@ -124,8 +130,8 @@ int32_t validate_mlp(const dip_mlp* mlp, int k_in, int k_mid) {
     if (mlp->w_ug.n_out != 2 * f) return fail(DIP_ERR_INVALID_ARG, "w_ug.n_out must be 2 * w_d.n_in (bundled up/gate)");
     if (mlp->w_d.n_out != d) return fail(DIP_ERR_INVALID_ARG, "w_d.n_out must equal w_ug.n_in");
     if (d > DIP_MAX_N || f > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "d_model and d_ff must be <= %d", DIP_MAX_N);
-    const int eb = elem_bytes(mlp->w_ug.dtype);
-    if (f % (16 / eb)) return fail(DIP_ERR_UNSUPPORTED, "d_ff must be a multiple of %d", 16 / eb);
+    const int per_load = mlp->w_ug.dtype == DIP_INT4_G128 ? 128 : 128 / elem_bits(mlp->w_ug.dtype);
+    if (f % per_load) return fail(DIP_ERR_UNSUPPORTED, "d_ff must be a multiple of %d", per_load);
     if (k_in < 1 || k_in > d) return fail(DIP_ERR_INVALID_ARG, "k_in must be in [1, d_model]");
     if (k_mid < 1 || k_mid > f) return fail(DIP_ERR_INVALID_ARG, "k_mid must be in [1, d_ff]");
     return DIP_OK;
@@ -165,7 +171,8 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     // gathered up/gate GEMV + SwiGLU
     GemvParams g1;
     std::memset(&g1, 0, sizeof(g1));
-    g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes; g1.dtype = mlp->w_ug.dtype;
+    g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes;
+    g1.scales = static_cast<const uint16_t*>(mlp->w_ug.scales); g1.scale_stride = mlp->w_ug.n_out / 128; g1.dtype = mlp->w_ug.dtype;
     g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.idx = idx1; g1.val = val1; g1.k = k_in; g1.out = h;
     g1.partial = part_ug; g1.counters = cnt_ug;
     st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
@@ -188,7 +195,8 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     // gathered down GEMV
     GemvParams g2;
     std::memset(&g2, 0, sizeof(g2));
-    g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes; g2.dtype = mlp->w_d.dtype;
+    g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes;
+    g2.scales = static_cast<const uint16_t*>(mlp->w_d.scales); g2.scale_stride = mlp->w_d.n_out / 128; g2.dtype = mlp->w_d.dtype;
     g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.idx = idx2; g2.val = val2; g2.k = k_mid; g2.out = y;
     g2.partial = part_dn; g2.counters = cnt_dn;
     return check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
@@ -257,7 +265,7 @@ int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void
 
 size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k) {
     if (!w || w->n_out < 1 || k < 1) return 0;
-    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16) return 0;
+    if (w->dtype != DIP_F32 && w->dtype != DIP_BF16 && w->dtype != DIP_INT4_G128) return 0;
     const GemvShape s = choose_gemv_shape(w->dtype, w->n_out, 1, k);
     const int strips = gemv_strips(s, w->dtype, w->n_out);
     size_t bytes = align_up(sizeof(uint32_t) * strips, 256);
@@ -286,7 +294,8 @@ int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* id
     }
     GemvParams p;
     std::memset(&p, 0, sizeof(p));
-    p.w = w->data; p.row_stride = w->row_stride_bytes; p.dtype = w->dtype; p.n_in = w->n_in; p.n_out = w->n_out;
+    p.w = w->data; p.row_stride = w->row_stride_bytes; p.dtype = w->dtype;
+    p.scales = static_cast<const uint16_t*>(w->scales); p.scale_stride = w->n_out / 128; p.n_in = w->n_in; p.n_out = w->n_out;
     p.nseg = 1; p.idx = idx; p.val = nullptr; p.x_full = x; p.k = k; p.out = y_out;
     p.partial = partial; p.counters = counters;
     return check_hip(launch_gemv(p, s, hs, DIP_KERNEL_GEMV_DOWN), "dip_gathered_gemv");

@@ -27,9 +27,13 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename WT>
 struct Elem;
+struct q4_t {};  // tag: signed 4-bit codes, one fp16 scale per 128 consecutive elements of a row
+
 template <>
 struct Elem<float> {
     static constexpr int kPerLoad = 4;
+    static constexpr int kBits = 32;
+    static constexpr bool kScaled = false;
     __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[4]) {
         f[0] = __uint_as_float(q.x);
         f[1] = __uint_as_float(q.y);
@@ -40,6 +44,8 @@ struct Elem<float> {
 template <>
 struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
     static constexpr int kPerLoad = 8;
+    static constexpr int kBits = 16;
+    static constexpr bool kScaled = false;
     __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[8]) {
         f[0] = __uint_as_float(q.x << 16);
         f[1] = __uint_as_float(q.x & 0xffff0000u);
@@ -51,6 +57,27 @@ struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
         f[7] = __uint_as_float(q.w & 0xffff0000u);
     }
 };
+
+template <>
+struct Elem<q4_t> {  // 32 codes per 16-byte load, low nibble = even element; value = code (scale applied by the caller)
+    static constexpr int kPerLoad = 32;
+    static constexpr int kBits = 4;
+    static constexpr bool kScaled = true;
+    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[32]) {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int n = 0; n < 8; ++n)   // shift the nibble to the top, arithmetic shift back: sign-extended code, then int -> float
+                f[i * 8 + n] = (float)(((int)(w[i] << (28 - 4 * n))) >> 28);
+    }
+};
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
+    _Float16 v;
+    __builtin_memcpy(&v, &h, 2);
+    return (float)v;
+}
 
 __device__ __forceinline__ u32x4 load16(const char* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
@@ -83,8 +110,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[s][e] = 0.f;
 
-    const char* wbase = static_cast<const char*>(p.w) + (size_t)col * sizeof(WT);
-    const size_t seg_bytes = (size_t)p.n_out * sizeof(WT);
+    const char* wbase = static_cast<const char*>(p.w) + (size_t)col * Elem<WT>::kBits / 8;
+    const size_t seg_bytes = (size_t)p.n_out * Elem<WT>::kBits / 8;
+    // quantised rows: the scale of this lane's 32 codes (all inside one group of 128)
+    const int sgroup = col >> 7, sgroups_per_seg = p.n_out >> 7;
     constexpr int NG = WAVES * RPW;            // lane groups per workgroup
     constexpr int ROWS_PER_ITER = UNROLL * NG;
 
@@ -134,13 +163,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     if (n_full > 0) fetch_full(t0);
     for (int it = 0; it < n_full; ++it) {
         u32x4 q[UNROLL][NSEG];
+        uint16_t sc[UNROLL][NSEG];
         float xc[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const size_t off = (size_t)row[u] * (size_t)p.row_stride;
             xc[u] = xv[u];
 #pragma unroll
-            for (int s = 0; s < NSEG; ++s) q[u][s] = load16(wbase + off + s * seg_bytes);
+            for (int s = 0; s < NSEG; ++s) {
+                q[u][s] = load16(wbase + off + s * seg_bytes);
+                if constexpr (Elem<WT>::kScaled)
+                    sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
+            }
         }
         t0 += ROWS_PER_ITER;
         if (it + 1 < n_full) fetch_full(t0);
@@ -150,14 +184,17 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             for (int s = 0; s < NSEG; ++s) {
                 float f[EPL];
                 Elem<WT>::widen(q[u][s], f);
+                float mult = xc[u];
+                if constexpr (Elem<WT>::kScaled) mult *= half_bits_to_float(sc[u][s]);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], xc[u], acc[s][e]);
+                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
             }
         }
     }
     // Tail: fewer than ROWS_PER_ITER rows are left; rows past the end are skipped.
     if (col_ok && t0 < ke) {
         u32x4 q[UNROLL][NSEG];
+        uint16_t sc[UNROLL][NSEG];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int t = t0 + u;
@@ -176,8 +213,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
                 q[u][s] = u32x4{0u, 0u, 0u, 0u};
-                if (row[u] >= 0)
+                sc[u][s] = 0;
+                if (row[u] >= 0) {
                     q[u][s] = load16(wbase + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
+                    if constexpr (Elem<WT>::kScaled)
+                        sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
+                }
             }
         }
 #pragma unroll
@@ -186,8 +227,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             for (int s = 0; s < NSEG; ++s) {
                 float f[EPL];
                 Elem<WT>::widen(q[u][s], f);
+                float mult = xv[u];
+                if constexpr (Elem<WT>::kScaled) mult *= half_bits_to_float(sc[u][s]);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], xv[u], acc[s][e]);
+                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
             }
         }
     }
@@ -323,8 +366,10 @@ hipError_t launch_lpr(const GemvParams& p, const GemvShape& s, hipStream_t strea
 
 }  // namespace
 
+static int elems_per_load(int dtype) { return dtype == DIP_F32 ? 4 : (dtype == DIP_BF16 ? 8 : 32); }
+
 int gemv_strips(const GemvShape& s, int dtype, int n_out) {
-    const int epl = dtype == DIP_F32 ? 4 : 8;
+    const int epl = elems_per_load(dtype);
     const int sc = s.lpr * epl;
     return (n_out + sc - 1) / sc;
 }
@@ -335,11 +380,12 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     // enough row splits that a workgroup streams a few hundred rows -- long enough to
     // amortise its prologue and reduction, short enough to fill 256 compute units.
     GemvShape s;
-    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : 16;
+    const bool q4 = dtype == DIP_INT4_G128;   // 32 codes per lane: narrower strips, fewer rows in flight
+    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : (q4 ? 8 : 16);
     s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
-    s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
+    s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : (q4 ? 2 : 4);
     // a bundled strip needs 2*SC lanes for its epilogue
-    const int epl = dtype == DIP_F32 ? 4 : 8;
+    const int epl = elems_per_load(dtype);
     while (nseg * s.lpr * epl > s.waves * 64 && s.waves < 16) s.waves *= 2;
     if (g_gemv_override.ksplit) {
         s.ksplit = g_gemv_override.ksplit;
@@ -365,6 +411,7 @@ hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t str
     p.rows_per_split = ((p.k + s.ksplit - 1) / s.ksplit + 7) / 8 * 8;   // keeps vector index loads aligned
     if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream, pk);
     if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
+    if (p.dtype == DIP_INT4_G128) return launch_lpr<q4_t>(p, s, stream, pk);
     return hipErrorInvalidValue;
 }
 

@@ -81,6 +81,8 @@ struct GemvShape {
 struct GemvParams {
     const void* w;            // feature-major weights
     int64_t row_stride;       // bytes
+    const uint16_t* scales;   // DIP_INT4_G128: fp16 bit patterns, scale_stride per stored row
+    int scale_stride;
     int dtype;                // DIP_F32 | DIP_BF16
     int n_in;                 // stored rows
     int n_out;                // elements per row actually produced per segment

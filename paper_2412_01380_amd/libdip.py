@@ -140,20 +140,33 @@ def _stream(stream) -> Optional[int]:
 
 class Weight:
     """A feature-major weight matrix on the device: tensor [n_in][n_out], fp32 or bf16
-    (bf16 may be given as torch.bfloat16, int16 or uint16 holding the bit patterns)."""
+    (bf16 may be given as torch.bfloat16, int16 or uint16 holding the bit patterns), or
+    int4-g128: `data` uint8 [n_in][n_out/2] (low nibble = even element) with `scales`
+    float16 [n_in][n_out/128]."""
 
-    def __init__(self, data):
+    def __init__(self, data, scales=None):
         import torch
         if data.dim() != 2 or not data.is_cuda or data.stride(1) != 1:
             raise TypeError("weight must be a 2-D device tensor with unit inner stride")
-        if data.dtype == torch.float32:
+        n_out = data.shape[1]
+        sptr = None
+        if scales is not None:
+            if data.dtype != torch.uint8 or scales.dtype != torch.float16:
+                raise TypeError("int4 weights are uint8 codes with float16 scales")
+            n_out = data.shape[1] * 2
+            if (not scales.is_cuda or not scales.is_contiguous()
+                    or tuple(scales.shape) != (data.shape[0], n_out // 128)):
+                raise TypeError("scales must be a contiguous device tensor [n_in][n_out/128]")
+            dt = DIP_INT4_G128
+            sptr = scales.data_ptr()
+        elif data.dtype == torch.float32:
             dt = DIP_F32
         elif data.dtype in (torch.bfloat16, torch.int16, torch.uint16):
             dt = DIP_BF16
         else:
             raise TypeError(f"unsupported weight dtype {data.dtype}")
-        self.tensor = data
-        self.c = _Weight(data.data_ptr(), None, dt, data.shape[0], data.shape[1], 0,
+        self.tensor, self.scales = data, scales
+        self.c = _Weight(data.data_ptr(), sptr, dt, data.shape[0], n_out, 0,
                          data.stride(0) * data.element_size())
 
 

@@ -29,8 +29,11 @@ def dev_f32(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def dev_weight(w: np.ndarray) -> torch.Tensor:
-    """fp32 array or uint16 bf16 bit patterns -> device tensor the binding accepts."""
+def dev_weight(w):
+    """fp32 array, uint16 bf16 bit patterns, or an int4 (codes, scales) pair -> what
+    paper_2412_01380_amd.Weight(...) accepts (a tensor, or a (codes, scales) tuple of tensors)."""
+    if isinstance(w, tuple):
+        return (torch.from_numpy(w[0]).cuda(), torch.from_numpy(w[1]).cuda())
     if w.dtype == np.uint16:
         return torch.from_numpy(w.view(np.int16).copy()).cuda()
     return torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).cuda()
@@ -44,3 +47,9 @@ def rel_l2(a, b) -> float:
 
 def workspace(nbytes: int) -> torch.Tensor:
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+
+
+def make_weight(D, w):
+    """Device Weight descriptor for any stored format of workloads.layer_weights."""
+    t = dev_weight(w)
+    return D.Weight(*t) if isinstance(t, tuple) else D.Weight(t)

@@ -75,7 +75,7 @@ def test_gemv_argument_validation(D):
     assert call(w, ws=None) == D.DIP_ERR_WORKSPACE
     assert call(w, wsb=8) == D.DIP_ERR_WORKSPACE
     assert call(w, ws=FAKE + 4) == D.DIP_ERR_WORKSPACE
-    assert call(_weight(D, dtype=2)) == D.DIP_ERR_UNSUPPORTED          # int4 not implemented
+    assert call(_weight(D, dtype=2, n_out=128)) == D.DIP_ERR_INVALID_ARG   # int4 without scales
     assert call(_weight(D, dtype=7)) == D.DIP_ERR_UNSUPPORTED
     assert call(_weight(D, n_out=66)) == D.DIP_ERR_UNSUPPORTED         # not a 16-byte multiple
     assert call(_weight(D, stride=100)) == D.DIP_ERR_INVALID_ARG       # stride < row

@@ -15,11 +15,11 @@ import torch
 from oracle import dip_oracle as O
 from workloads import CONFIGS, ar1_laplace_stream, layer_weights, studentt_tokens
 from gpu_util import (bits_from_bool, bool_from_bits, dev_f32, dev_u32, dev_weight, host_u32,
-                      rel_l2, workspace)
+                      make_weight, rel_l2, workspace)
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-3}
+TOL = {"f32": 1e-5, "bf16": 2e-3, "int4": 2e-3}   # int4: dequantisation is exact in fp32, bf16 bar
 
 
 @pytest.fixture(scope="module")
@@ -270,7 +270,7 @@ def _stage_replay(D, w, x, k_in, k_mid, tol, cache_pair=None, oracle_caches=None
 
 def _setup_layer(D, d, f, fmt, seed, layer, k_in, k_mid):
     w = layer_weights(d, f, seed=seed, layer=layer, dtype=fmt)
-    mlp = D.Mlp(D.Weight(dev_weight(w["ug"])), D.Weight(dev_weight(w["d"])))
+    mlp = D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"]))
     ws = workspace(D.dip_swiglu_mlp_forward_workspace_bytes(mlp, k_in, k_mid))
     return {"ug": w["ug"], "d": w["d"], "mlp": mlp, "ws": ws,
             "dbg": D.Debug(d, f, k_in, k_mid),
@@ -388,3 +388,51 @@ def test_stack_call_equals_per_layer_calls(D):
                                   layers[l]["y"].cpu().numpy().view(np.uint32))
             assert np.array_equal(host_u32(cins[l].bits), host_u32(cins2[l].bits))
             assert np.array_equal(host_u32(cmids[l].stamp), host_u32(cmids2[l].stamp))
+
+
+# ------------------------------------------------------------------ int4-g128 weights (batch 1)
+@pytest.mark.parametrize("n_in,n_out,k", [(64, 128, 1), (300, 256, 111), (1536, 512, 768), (777, 1152, 300)])
+def test_gathered_gemv_int4_matches_oracle(D, n_in, n_out, k):
+    from workloads import pack_int4_g128
+    rng = np.random.default_rng(n_in + n_out)
+    w = pack_int4_g128((rng.standard_normal((n_in, n_out)) * 0.02).astype(np.float32))
+    x = studentt_tokens(1, n_in, seed=n_out)[0]
+    _, idx = O.topk(np.abs(x), k)
+    W = make_weight(D, w)
+    y = torch.empty(n_out, dtype=torch.float32, device="cuda")
+    ws = workspace(D.dip_gathered_gemv_workspace_bytes(W, k))
+    D.dip_gathered_gemv(W, dev_f32(x), torch.from_numpy(idx.astype(np.int32)).cuda(), k, y, ws)
+    assert rel_l2(y.cpu().numpy(), O.gathered_gemv(w, x, idx)) <= TOL["int4"]
+    if k == 1:   # a unit multiplier returns the dequantised row exactly
+        x1 = np.zeros(n_in, dtype=np.float32)
+        x1[idx[0]] = 1.0
+        D.dip_gathered_gemv(W, dev_f32(x1), torch.from_numpy(idx.astype(np.int32)).cuda(), 1, y, ws)
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), O.widen_rows(w, idx)[0])
+
+
+def test_forward_int4_small_with_cache(D):
+    d, f, k_in, k_mid = 512, 1536, 154, 461
+    w = _setup_layer(D, d, f, "int4", 21, 0, k_in, k_mid)
+    cin, cmid = D.Cache(d, d // 2), D.Cache(f, f // 2)
+    D.dip_cache_init(cin)
+    D.dip_cache_init(cmid)
+    ocin, ocmid = O.CacheState(n=d, capacity=d // 2), O.CacheState(n=f, capacity=f // 2)
+    xs = ar1_laplace_stream(6, d, seed=9)
+    for t in range(6):
+        _stage_replay(D, w, xs[t], k_in, k_mid, TOL["int4"], (cin, cmid), (ocin, ocmid), 0.2)
+
+
+def test_config5_phi3_medium_int4_batch1(D):
+    cfg = CONFIGS[5]
+    d, f = cfg.d_model, cfg.d_ff
+    k_in, k_mid = cfg.k_in(0.3), cfg.k_mid(0.3)
+    assert (k_in, k_mid) == (1536, 5376)
+    w = _setup_layer(D, d, f, "int4", cfg.seed, 0, k_in, k_mid)
+    C_in, C_mid = d // 2, f // 2
+    cin, cmid = D.Cache(d, C_in), D.Cache(f, C_mid)
+    D.dip_cache_init(cin)
+    D.dip_cache_init(cmid)
+    ocin, ocmid = O.CacheState(n=d, capacity=C_in), O.CacheState(n=f, capacity=C_mid)
+    xs = cfg.tokens(n_tokens=4)
+    for t in range(4):
+        _stage_replay(D, w, xs[t], k_in, k_mid, TOL["int4"], (cin, cmid), (ocin, ocmid), cfg.gamma)
