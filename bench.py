@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=4096)
     ap.add_argument("--warmup", type=int, default=256)
-    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4))
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5))
     ap.add_argument("--ratio", type=float, default=None, help="keep ratio at both pruning points")
     ap.add_argument("--cache-frac", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None,
@@ -76,13 +76,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = CONFIGS[a.config]
-    r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3}[a.config]
+    r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3, 5: 0.3}[a.config]
     frac = a.cache_frac if a.cache_frac is not None else cfg.cache_fracs[0]
     d, f = cfg.d_model, cfg.d_ff
     k_in, k_mid = cfg.k_in(r), cfg.k_mid(r)
     # config 2 is one layer shape: rotate over distinct weight copies so that the 256 MB
     # last-level cache cannot serve the reads; configs 3/4 are real stacks.
-    L = a.layers if a.layers is not None else {2: 8, 3: cfg.n_layers, 4: cfg.n_layers}[a.config]
+    L = a.layers if a.layers is not None else {2: 8}.get(a.config, cfg.n_layers)
     n_tok = cfg.n_tokens
 
     t_setup = time.perf_counter()
@@ -92,8 +92,11 @@ def main():
         w = layer_weights(d, f, cfg.seed, l, cfg.dtype)
         if l < 1:
             host_w.append(w)          # the oracle sample uses layer 0
-        dev = lambda arr: torch.from_numpy(arr.view(np.int16)).cuda()
-        mlps.append(D.Mlp(D.Weight(dev(w["ug"])), D.Weight(dev(w["d"]))))
+        if cfg.dtype == "int4":
+            mk = lambda t: D.Weight(torch.from_numpy(t[0]).cuda(), torch.from_numpy(t[1]).cuda())
+        else:
+            mk = lambda arr: D.Weight(torch.from_numpy(arr.view(np.int16)).cuda())
+        mlps.append(D.Mlp(mk(w["ug"]), mk(w["d"])))
         del w
     # inputs: [token][layer][d]; every layer has its own stream (layers are not chained)
     X = np.stack([cfg.tokens(layer=l, n_tokens=n_tok) for l in range(L)], axis=1)
@@ -130,9 +133,10 @@ def main():
     wall = time.perf_counter() - t0
 
     gathered = cfg.gathered_bytes(r)
-    ug_bytes = 2 * k_in * f * 2
-    dn_bytes = k_mid * d * 2
-    tokens_per_s = steps / wall if a.config == 2 else passes / wall
+    bytes_of = (lambda e: e // 2 + (e // 128) * 2) if cfg.dtype == "int4" else (lambda e: e * 2)
+    ug_bytes = bytes_of(2 * k_in * f)
+    dn_bytes = bytes_of(k_mid * d)
+    tokens_per_s = steps / wall if a.config == 2 else passes / wall   # configs 3-5: L layers per token
     out = {
         "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
         "value": tokens_per_s,
@@ -148,7 +152,7 @@ def main():
                         + f", {L} " + ("distinct weight copies visited round-robin" if a.config == 2
                                         else "layers per token"),
             "inputs": cfg.inputs, "weights_dtype": cfg.dtype,
-            "weight_bytes_resident": int(L * 3 * d * f * 2),
+            "weight_bytes_resident": int(L * bytes_of(3 * d * f)),
             "gathered_bytes_per_step": gathered,
             "step": "one token through one MLP layer (4 kernel launches)",
         },

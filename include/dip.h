@@ -58,8 +58,9 @@ typedef enum dip_dtype {
     DIP_F32 = 0,      /* fp32 weights                                                       */
     DIP_BF16 = 1,     /* bfloat16 weights, widened exactly to fp32 before the multiply      */
     DIP_INT4_G128 = 2 /* signed 4-bit codes, one fp16 scale per 128 consecutive elements of
-                         a stored row, w = scale * q; low nibble = even element.
-                         (Reserved: not implemented by this version.)                       */
+                         a stored row (dip_weight.scales: n_out/128 per row, rows back to
+                         back), w = scale * q; two codes per byte, low nibble = even
+                         element; n_out must be a multiple of 128                           */
 } dip_dtype;
 
 typedef enum dip_policy {
@@ -178,7 +179,7 @@ int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void
  * Column-gathered matrix-vector product, Alg. 1 step 4 (W~ = W (.) m) applied to x:
  *     y[j] = sum_{t<k} W[j, idx[t]] * x[idx[t]]        fp32 accumulation.
  * The summation order is fixed by the launch configuration, so results are bit-repeatable.
- *   w        feature-major matrix (F32 or BF16); n_out % (16 / element size) == 0
+ *   w        feature-major matrix (F32, BF16 or INT4_G128); a row is whole 16-byte loads
  *   x        w->n_in floats        idx   k ascending indices in [0, n_in), 1 <= k <= n_in
  *   y_out    w->n_out floats       ws    dip_gathered_gemv_workspace_bytes() bytes, 256-aligned
  */

@@ -59,17 +59,29 @@ struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
 };
 
 template <>
-struct Elem<q4_t> {  // 32 codes per 16-byte load, low nibble = even element; value = code (scale applied by the caller)
+struct Elem<q4_t> {
+    // 32 codes per 16-byte load, low nibble = even element.  Flipping bit 3 of every nibble
+    // turns the two's-complement code q into q + 8 in [0, 15]; masking even and odd nibbles
+    // apart leaves them as bytes, which convert to float in one instruction each.  The
+    // caller removes the offset: sum (q + 8) m - 8 sum m.
     static constexpr int kPerLoad = 32;
     static constexpr int kBits = 4;
     static constexpr bool kScaled = true;
     __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[32]) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t o = w[i] ^ 0x88888888u;
+            uint32_t ev = o & 0x0f0f0f0fu, od = (o >> 4) & 0x0f0f0f0fu;
+            // keep the compiler from narrowing the byte extracts below into bit-field
+            // extracts: a byte of a register converts to float in one instruction
+            asm volatile("" : "+v"(ev), "+v"(od));
 #pragma unroll
-            for (int n = 0; n < 8; ++n)   // shift the nibble to the top, arithmetic shift back: sign-extended code, then int -> float
-                f[i * 8 + n] = (float)(((int)(w[i] << (28 - 4 * n))) >> 28);
+            for (int b = 0; b < 4; ++b) {
+                f[i * 8 + 2 * b] = (float)((ev >> (8 * b)) & 0xffu);
+                f[i * 8 + 2 * b + 1] = (float)((od >> (8 * b)) & 0xffu);
+            }
+        }
     }
 };
 
@@ -105,10 +117,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     const int ke = min(p.k, kb + p.rows_per_split);
 
     float acc[NSEG][EPL];
+    float msum[NSEG];   // quantised rows: sum of the row multipliers, for the code offset
 #pragma unroll
-    for (int s = 0; s < NSEG; ++s)
+    for (int s = 0; s < NSEG; ++s) {
+        msum[s] = 0.f;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[s][e] = 0.f;
+    }
 
     const char* wbase = static_cast<const char*>(p.w) + (size_t)col * Elem<WT>::kBits / 8;
     const size_t seg_bytes = (size_t)p.n_out * Elem<WT>::kBits / 8;
@@ -185,7 +200,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
                 float f[EPL];
                 Elem<WT>::widen(q[u][s], f);
                 float mult = xc[u];
-                if constexpr (Elem<WT>::kScaled) mult *= half_bits_to_float(sc[u][s]);
+                if constexpr (Elem<WT>::kScaled) {
+                    mult *= half_bits_to_float(sc[u][s]);
+                    msum[s] += mult;
+                }
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
             }
@@ -228,11 +246,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
                 float f[EPL];
                 Elem<WT>::widen(q[u][s], f);
                 float mult = xv[u];
-                if constexpr (Elem<WT>::kScaled) mult *= half_bits_to_float(sc[u][s]);
+                if constexpr (Elem<WT>::kScaled) {
+                    mult *= half_bits_to_float(sc[u][s]);
+                    msum[s] += mult;
+                }
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
             }
         }
+    }
+
+    if constexpr (Elem<WT>::kScaled) {
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(-8.0f, msum[s], acc[s][e]);
     }
 
     // lane groups of one wavefront
@@ -383,7 +411,7 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     const bool q4 = dtype == DIP_INT4_G128;   // 32 codes per lane: narrower strips, fewer rows in flight
     s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : (q4 ? 8 : 16);
     s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
-    s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : (q4 ? 2 : 4);
+    s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
     // a bundled strip needs 2*SC lanes for its epilogue
     const int epl = elems_per_load(dtype);
     while (nseg * s.lpr * epl > s.waves * 64 && s.waves < 16) s.waves *= 2;
@@ -391,10 +419,11 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
         s.ksplit = g_gemv_override.ksplit;
     } else {
         const int strips = gemv_strips(s, dtype, n_out);
-        const int rows_per_wg = nseg == 2 ? 384 : 512;
+        // (int4 rows are a quarter of the bytes and the reduction costs the same: longer shares)
+        const int rows_per_wg = q4 ? (nseg == 2 ? 768 : 640) : (nseg == 2 ? 384 : 512);
         int ks = (k + rows_per_wg / 2) / rows_per_wg;
         if (ks < 1) ks = 1;
-        const int min_wgs = 192;
+        const int min_wgs = q4 ? 128 : 192;
         if (strips * ks < min_wgs) ks = (min_wgs + strips - 1) / strips;
         // but keep at least one full iteration of rows per workgroup
         const int rows_per_iter = s.waves * (64 / s.lpr) * s.unroll;

@@ -163,9 +163,11 @@ class WorkloadConfig:
         return k_from_ratio(r, self.d_ff)
 
     def gathered_bytes(self, r: float) -> int:
-        """Weight bytes one layer-token must read (bf16/f32; scales excluded)."""
-        bw = {"f32": 4, "bf16": 2}[self.dtype]
-        return (2 * self.k_in(r) * self.d_ff + self.k_mid(r) * self.d_model) * bw
+        """Weight bytes one layer-token must read at batch 1 (int4: codes plus fp16 group scales)."""
+        elems = 2 * self.k_in(r) * self.d_ff + self.k_mid(r) * self.d_model
+        if self.dtype == "int4":
+            return elems // 2 + (elems // 128) * 2
+        return elems * {"f32": 4, "bf16": 2}[self.dtype]
 
     def tokens(self, layer: int = 0, n_tokens: Optional[int] = None, n: Optional[int] = None):
         """Input stream for one layer (layers get independent streams, not chained)."""
