@@ -220,6 +220,26 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
                                      size_t ws_bytes, void* stream);
 
 /*
+ * A small decode batch through one layer: `batch` (1..8) rows X[b] (row stride d_model)
+ * give `batch` independent batch-1 results Y[b] of dip_swiglu_mlp_forward -- every row has
+ * its own two top-K masks -- while each stored column is read once if any row selected it
+ * (the union of the row masks) and is accumulated only into the rows that selected it.
+ * All rows are scored against the cache state from before the step; each cache is then
+ * updated once with the union mask (Alg. 1 step 3).  The paper itself is batch 1 (Sec. 1).
+ * Optional outputs for stage-wise comparison (each may be NULL):
+ *   mask_in_out   [batch][ceil(d_model/32)] words     h_out  [batch][d_ff] floats
+ *   mask_mid_out  [batch][ceil(d_ff/32)] words
+ * Summation order is fixed by the launch configuration (bit-repeatable).
+ */
+size_t dip_swiglu_mlp_forward_batched_workspace_bytes(const dip_mlp* mlp, int32_t batch,
+                                                      int32_t k_in, int32_t k_mid);
+int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32_t batch,
+                                       int32_t k_in, int32_t k_mid, const dip_cache* cache_in,
+                                       const dip_cache* cache_mid, float gamma, float* Y,
+                                       uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out,
+                                       void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Launch-shape override for the gathered GEMV kernels, for tuning sweeps.  0 restores the
  * built-in choice for that parameter.  Host-side, process-wide, not thread-safe against
  * concurrent launches.

@@ -12,5 +12,6 @@ from .libdip import (  # noqa: F401
     dip_gathered_gemv_workspace_bytes, dip_last_error, dip_prune_topk,
     dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack,
     dip_swiglu_mlp_forward_workspace_bytes, dip_tune_gemv, dip_version, MlpStack, EXPORTS, META,
-    dip_gemv_launch_shape, dip_profile_enable, dip_profile_read, dip_profile_disable,
+    dip_gemv_launch_shape, dip_profile_enable,
+    dip_swiglu_mlp_forward_batched, dip_swiglu_mlp_forward_batched_workspace_bytes, dip_profile_read, dip_profile_disable,
 )

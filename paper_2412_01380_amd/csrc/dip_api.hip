@@ -1,6 +1,7 @@
 // C ABI of libdip: argument validation on the host, then kernel launches on the caller's
 // stream.  Nothing here allocates device memory, synchronises, or reads device data.
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -358,6 +359,129 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
                                      size_t ws_bytes, void* stream) {
     return forward_checked(mlps, n_layers, x, x_stride, k_in, k_mid, caches_in, caches_mid, gamma,
                            y_out, y_stride, nullptr, ws, ws_bytes, stream);
+}
+
+namespace {
+struct BatchedPlan {
+    int d, f, wd, wf, k1max, k2max, g1, g2;
+    size_t off_m1, off_u1, off_idx1, off_val1, off_m2, off_u2, off_idx2, off_val2, off_cnt, off_h,
+        off_part;
+    size_t total;
+};
+BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
+    BatchedPlan pl;
+    pl.d = mlp->w_ug.n_in; pl.f = mlp->w_d.n_in;
+    pl.wd = (pl.d + 31) / 32; pl.wf = (pl.f + 31) / 32;
+    pl.k1max = std::min(pl.d, B * k_in);
+    pl.k2max = std::min(pl.f, B * k_mid);
+    pl.g1 = batched_shares(mlp->w_ug.dtype, 2 * pl.f, pl.k1max);
+    pl.g2 = batched_shares(mlp->w_d.dtype, pl.d, pl.k2max);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    pl.off_m1 = take(sizeof(uint32_t) * B * pl.wd);
+    pl.off_u1 = take(sizeof(uint32_t) * pl.wd);
+    pl.off_idx1 = take(sizeof(int32_t) * pl.k1max);
+    pl.off_val1 = take(sizeof(float) * (size_t)pl.k1max * B);
+    pl.off_m2 = take(sizeof(uint32_t) * B * pl.wf);
+    pl.off_u2 = take(sizeof(uint32_t) * pl.wf);
+    pl.off_idx2 = take(sizeof(int32_t) * pl.k2max);
+    pl.off_val2 = take(sizeof(float) * (size_t)pl.k2max * B);
+    pl.off_cnt = take(sizeof(uint32_t) * 2);
+    pl.off_h = take(sizeof(float) * (size_t)B * pl.f);
+    const size_t p1 = sizeof(float) * (size_t)pl.g1 * B * 2 * pl.f;
+    const size_t p2 = sizeof(float) * (size_t)pl.g2 * B * pl.d;
+    pl.off_part = take(std::max(p1, p2));
+    pl.total = o;
+    return pl;
+}
+}  // namespace
+
+size_t dip_swiglu_mlp_forward_batched_workspace_bytes(const dip_mlp* mlp, int32_t batch,
+                                                      int32_t k_in, int32_t k_mid) {
+    if (batch < 1 || batch > 8 || validate_mlp(mlp, k_in, k_mid)) return 0;
+    return plan_batched(mlp, batch, k_in, k_mid).total;
+}
+
+int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32_t batch,
+                                       int32_t k_in, int32_t k_mid, const dip_cache* cache_in,
+                                       const dip_cache* cache_mid, float gamma, float* Y,
+                                       uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out,
+                                       void* ws, size_t ws_bytes, void* stream) {
+    if (batch < 1 || batch > 8) return fail(DIP_ERR_INVALID_ARG, "forward_batched: batch must be in [1, 8]");
+    int32_t st = validate_mlp(mlp, k_in, k_mid);
+    if (st) return st;
+    if (!X || !Y) return fail(DIP_ERR_INVALID_ARG, "forward_batched: null X or Y");
+    if (cache_in || cache_mid) {
+        if ((st = validate_gamma(gamma))) return st;
+    }
+    if (cache_in && (st = validate_cache(cache_in, mlp->w_ug.n_in, "cache_in"))) return st;
+    if (cache_mid && (st = validate_cache(cache_mid, mlp->w_d.n_in, "cache_mid"))) return st;
+    const BatchedPlan pl = plan_batched(mlp, batch, k_in, k_mid);
+    if (!ws || ws_bytes < pl.total || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "forward_batched: workspace must be 256-aligned and >= %zu bytes", pl.total);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(base + pl.off_cnt);
+    float* H = h_out ? h_out : reinterpret_cast<float*>(base + pl.off_h);
+    float* part = reinterpret_cast<float*>(base + pl.off_part);
+
+    struct Point {
+        const float* v; int n, k, kmax, words; const dip_cache* cache; uint32_t* masks; uint32_t* uwords;
+        int32_t* uidx; float* uval; uint32_t* count; int kind;
+    };
+    const Point pts[2] = {
+        {X, pl.d, k_in, pl.k1max, pl.wd, cache_in,
+         mask_in_out ? mask_in_out : reinterpret_cast<uint32_t*>(base + pl.off_m1),
+         reinterpret_cast<uint32_t*>(base + pl.off_u1), reinterpret_cast<int32_t*>(base + pl.off_idx1),
+         reinterpret_cast<float*>(base + pl.off_val1), cnt, DIP_KERNEL_SELECT_IN},
+        {H, pl.f, k_mid, pl.k2max, pl.wf, cache_mid,
+         mask_mid_out ? mask_mid_out : reinterpret_cast<uint32_t*>(base + pl.off_m2),
+         reinterpret_cast<uint32_t*>(base + pl.off_u2), reinterpret_cast<int32_t*>(base + pl.off_idx2),
+         reinterpret_cast<float*>(base + pl.off_val2), cnt + 1, DIP_KERNEL_SELECT_MID}};
+    for (int pt = 0; pt < 2; ++pt) {
+        const Point& q = pts[pt];
+        // per-row scores and masks (state of the cache from before the step)
+        SelectParams sp;
+        std::memset(&sp, 0, sizeof(sp));
+        sp.v = q.v; sp.n = q.n; sp.k = q.k; sp.gamma = gamma;
+        sp.score_bits = q.cache ? q.cache->bits : nullptr;
+        sp.mask_out = q.masks; sp.rows = batch; sp.v_row_stride = q.n; sp.words_row_stride = q.words;
+        if ((st = check_hip(launch_select(sp, hs, q.kind), "forward_batched: select"))) return st;
+        // union of the row masks, its index list and the row multipliers
+        UnionParams up;
+        std::memset(&up, 0, sizeof(up));
+        up.masks = q.masks; up.words_stride = q.words; up.x = q.v; up.x_stride = q.n; up.n = q.n;
+        up.batch = batch; up.union_words = q.uwords; up.uidx = q.uidx; up.uval = q.uval; up.count_out = q.count;
+        if ((st = check_hip(launch_union(up, hs), "forward_batched: union"))) return st;
+        // one cache update with the union mask
+        if (q.cache) {
+            SelectParams cp;
+            std::memset(&cp, 0, sizeof(cp));
+            cp.n = q.n; cp.k = 1; cp.mask_in = q.uwords;
+            cp.c_bits = q.cache->bits; cp.c_stamp = q.cache->stamp; cp.c_meta = q.cache->meta;
+            cp.capacity = q.cache->capacity; cp.policy = q.cache->policy;
+            if ((st = check_hip(launch_select(cp, hs, -1), "forward_batched: cache update"))) return st;
+        }
+        // gathered product for all rows, then the reduction with its epilogue
+        const dip_weight& w = pt == 0 ? mlp->w_ug : mlp->w_d;
+        const int shares = pt == 0 ? pl.g1 : pl.g2;
+        BatchedGemvParams gp;
+        std::memset(&gp, 0, sizeof(gp));
+        gp.w = w.data; gp.row_stride = w.row_stride_bytes;
+        gp.scales = static_cast<const uint16_t*>(w.scales); gp.scale_stride = w.n_out / 128;
+        gp.dtype = w.dtype; gp.n_in = w.n_in; gp.n_out = w.n_out;
+        gp.uidx = q.uidx; gp.uval = q.uval; gp.k_dev = q.count; gp.k_max = q.kmax; gp.batch = batch;
+        gp.partial = part;
+        if ((st = check_hip(launch_batched_gemv(gp, shares, hs, pt == 0 ? DIP_KERNEL_GEMV_UPGATE : DIP_KERNEL_GEMV_DOWN),
+                            "forward_batched: gathered product")))
+            return st;
+        BatchedReduceParams rp;
+        std::memset(&rp, 0, sizeof(rp));
+        rp.partial = part; rp.shares = shares; rp.batch = batch; rp.n_out = w.n_out; rp.glu = pt == 0 ? 1 : 0;
+        rp.out = pt == 0 ? H : Y; rp.out_stride = pt == 0 ? pl.f : pl.d;
+        if ((st = check_hip(launch_batched_reduce(rp, hs), "forward_batched: reduction"))) return st;
+    }
+    return DIP_OK;
 }
 
 int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll) {

@@ -56,6 +56,11 @@ struct SelectParams {
     // counters the following GEMV launch expects to be zero
     uint32_t* zero_ptr;
     int zero_n;
+    // rows > 1: one workgroup per row; row b reads v + b*v_row_stride and writes its mask at
+    // mask_out + b*words_row_stride (every other output and the cache update must be off)
+    int rows;
+    int64_t v_row_stride;
+    int64_t words_row_stride;
 };
 
 hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind);
@@ -102,6 +107,49 @@ int gemv_strips(const GemvShape& s, int dtype, int n_out);
 hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream, int prof_kind);
 
 extern GemvShape g_gemv_override;
+
+// ---- small batches: union of row masks, batched gathered product, reduction ------------------
+struct UnionParams {
+    const uint32_t* masks;     // [batch][words_stride]
+    int64_t words_stride;
+    const float* x;            // [batch][x_stride] activations the masks were taken from
+    int64_t x_stride;
+    int n;
+    int batch;
+    uint32_t* union_words;     // ceil(n/32)
+    int32_t* uidx;             // ascending indices of the union, up to min(n, batch*k)
+    float* uval;               // [listed][batch]: x[b][i] if row b selected i, else 0
+    uint32_t* count_out;       // number of listed indices
+};
+struct BatchedGemvParams {
+    const void* w;
+    int64_t row_stride;
+    const uint16_t* scales;
+    int scale_stride;
+    int dtype;
+    int n_in;
+    int n_out;                 // full stored row width
+    const int32_t* uidx;
+    const float* uval;
+    const uint32_t* k_dev;     // listed columns (device)
+    int k_max;                 // capacity of the lists
+    int batch;
+    float* partial;            // [shares][batch][n_out]
+};
+struct BatchedReduceParams {
+    const float* partial;
+    int shares;
+    int batch;
+    int n_out;
+    int glu;                   // 1: out = up * SiLU(gate) over the two halves of a row
+    float* out;
+    int64_t out_stride;
+};
+int batched_strip_cols(int dtype);
+int batched_shares(int dtype, int n_out, int k_max);
+hipError_t launch_union(const UnionParams& p, hipStream_t stream);
+hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int prof_kind);
+hipError_t launch_batched_reduce(const BatchedReduceParams& p, hipStream_t stream);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

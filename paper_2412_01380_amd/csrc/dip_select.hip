@@ -385,6 +385,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwords = (p.n + 31) >> 5;
     int phase = 0;
+    // one workgroup per row of a small batch (row 0 when there is no batch)
+    if (p.v) p.v += (size_t)blockIdx.x * p.v_row_stride;
+    if (p.mask_out) p.mask_out += (size_t)blockIdx.x * p.words_row_stride;
 
     for (int i = tid; i < p.zero_n; i += kSelThreads) p.zero_ptr[i] = 0u;
 
@@ -670,7 +673,7 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 
 template <int ITEMS>
 hipError_t launch_items(const SelectParams& p, hipStream_t stream, int prof_kind) {
-    return launch_timed(select_kernel<ITEMS>, dim3(1), dim3(kSelThreads), stream, prof_kind, p);
+    return launch_timed(select_kernel<ITEMS>, dim3(p.rows > 1 ? p.rows : 1), dim3(kSelThreads), stream, prof_kind, p);
 }
 
 }  // namespace

@@ -83,6 +83,11 @@ def _load() -> C.CDLL:
     L.dip_swiglu_mlp_forward_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, i32, i32,
                                                C.POINTER(_Cache), C.POINTER(_Cache), f32, vp, i64,
                                                vp, sz, vp]
+    L.dip_swiglu_mlp_forward_batched_workspace_bytes.restype = sz
+    L.dip_swiglu_mlp_forward_batched_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32, i32, i32]
+    L.dip_swiglu_mlp_forward_batched.restype = i32
+    L.dip_swiglu_mlp_forward_batched.argtypes = [C.POINTER(_Mlp), vp, i32, i32, i32, C.POINTER(_Cache),
+                                                 C.POINTER(_Cache), f32, vp, vp, vp, vp, vp, sz, vp]
     L.dip_tune_gemv.restype = i32
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
     L.dip_gemv_launch_shape.restype = i32
@@ -101,7 +106,8 @@ lib = _load()
 EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "dip_cache_init",
            "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
-           "dip_swiglu_mlp_forward_stack", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
+           "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
+           "dip_swiglu_mlp_forward_batched", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
            "dip_profile_disable"]
 
 
@@ -287,6 +293,22 @@ def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in: int, k
         stack.mlps, stack.n, _ptr(x, torch.float32), x_stride, k_in, k_mid, stack.cin, stack.cmid,
         gamma, _ptr(y_out, torch.float32), y_stride, _ptr(ws), ws.numel() * ws.element_size(),
         _stream(stream)))
+
+
+def dip_swiglu_mlp_forward_batched_workspace_bytes(mlp: Mlp, batch: int, k_in: int, k_mid: int) -> int:
+    return lib.dip_swiglu_mlp_forward_batched_workspace_bytes(C.byref(mlp.c), batch, k_in, k_mid)
+
+
+def dip_swiglu_mlp_forward_batched(mlp: Mlp, X, batch: int, k_in: int, k_mid: int,
+                                   cache_in: Optional[Cache], cache_mid: Optional[Cache], gamma: float,
+                                   Y, mask_in_out, h_out, mask_mid_out, ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_swiglu_mlp_forward_batched(
+        C.byref(mlp.c), _ptr(X, torch.float32), batch, k_in, k_mid,
+        C.byref(cache_in.c) if cache_in is not None else None,
+        C.byref(cache_mid.c) if cache_mid is not None else None,
+        gamma, _ptr(Y, torch.float32), _ptr(mask_in_out, torch.int32), _ptr(h_out, torch.float32),
+        _ptr(mask_mid_out, torch.int32), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:

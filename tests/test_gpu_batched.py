@@ -1,0 +1,103 @@
+"""GPU parity of the small-batch forward (B = 1..8 rows, unioned column reads) against the
+oracle, stage by stage on identical inputs as in test_gpu_parity.py: per-row masks are
+bit-exact, h~ and y within tolerance, caches identical to the oracle's update with the union
+of the row masks."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dip_oracle as O
+from workloads import CONFIGS, ar1_laplace_stream, layer_weights
+from gpu_util import bits_from_bool, bool_from_bits, dev_f32, host_u32, make_weight, rel_l2, workspace
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-3, "int4": 2e-3}
+
+
+@pytest.fixture(scope="module")
+def D():
+    import paper_2412_01380_amd as D
+    return D
+
+
+def run_steps(D, d, f, fmt, B, k_in, k_mid, steps, use_cache, seed, layer=0, cap_frac=0.5):
+    w = layer_weights(d, f, seed=seed, layer=layer, dtype=fmt)
+    mlp = D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"]))
+    ws = workspace(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlp, B, k_in, k_mid))
+    wd, wf = (d + 31) // 32, (f + 31) // 32
+    m1 = torch.empty(B, wd, dtype=torch.int32, device="cuda")
+    m2 = torch.empty(B, wf, dtype=torch.int32, device="cuda")
+    H = torch.empty(B, f, dtype=torch.float32, device="cuda")
+    Y = torch.empty(B, d, dtype=torch.float32, device="cuda")
+    cin = cmid = ocin = ocmid = None
+    if use_cache:
+        C_in, C_mid = int(cap_frac * d), int(cap_frac * f)
+        cin, cmid = D.Cache(d, C_in), D.Cache(f, C_mid)
+        D.dip_cache_init(cin)
+        D.dip_cache_init(cmid)
+        ocin, ocmid = O.CacheState(n=d, capacity=C_in), O.CacheState(n=f, capacity=C_mid)
+    # every row is its own AR(1) stream
+    streams = np.stack([ar1_laplace_stream(steps, d, seed=seed * 100 + b) for b in range(B)], axis=1)
+    for t in range(steps):
+        X = streams[t]
+        D.dip_swiglu_mlp_forward_batched(mlp, dev_f32(X), B, k_in, k_mid, cin, cmid, 0.2, Y, m1, H, m2, ws)
+        torch.cuda.synchronize()
+        Hg, Yg = H.cpu().numpy(), Y.cpu().numpy()
+        c_in = None if ocin is None else ocin.resident.copy()
+        c_mid = None if ocmid is None else ocmid.resident.copy()
+        M1, M2 = [], []
+        for b in range(B):
+            mb1, idx1 = O.topk(O.score(X[b], c_in, 0.2), k_in)
+            assert np.array_equal(host_u32(m1[b]), bits_from_bool(mb1)), (t, b, "mask 1")
+            h_ref = O.glu_from_preacts(O.gathered_gemv(w["ug"], X[b], idx1))
+            assert rel_l2(Hg[b], h_ref) <= TOL[fmt], (t, b, "h")
+            mb2, idx2 = O.topk(O.score(Hg[b], c_mid, 0.2), k_mid)
+            assert np.array_equal(host_u32(m2[b]), bits_from_bool(mb2)), (t, b, "mask 2")
+            y_ref = O.gathered_gemv(w["d"], Hg[b], idx2)
+            assert rel_l2(Yg[b], y_ref) <= TOL[fmt], (t, b, "y")
+            M1.append(mb1)
+            M2.append(mb2)
+        if use_cache:
+            O.cache_update(ocin, np.any(M1, axis=0))
+            O.cache_update(ocmid, np.any(M2, axis=0))
+            assert np.array_equal(bool_from_bits(host_u32(cin.bits), d), ocin.resident)
+            assert np.array_equal(host_u32(cin.stamp).astype(np.int64), ocin.stamp)
+            assert np.array_equal(bool_from_bits(host_u32(cmid.bits), f), ocmid.resident)
+            assert np.array_equal(host_u32(cmid.stamp).astype(np.int64), ocmid.stamp)
+            assert cmid.meta_host()["cum_lookups"] == ocmid.lookups
+    return Yg
+
+
+@pytest.mark.parametrize("fmt", ["f32", "bf16", "int4"])
+@pytest.mark.parametrize("B", [1, 2, 3, 8])
+def test_batched_small_layer(D, fmt, B):
+    run_steps(D, 512, 1536, fmt, B, 154, 461, steps=3, use_cache=True, seed=31)
+
+
+def test_batched_ragged_shapes_no_cache(D):
+    run_steps(D, 1000, 1144, "bf16", 5, 333, 401, steps=2, use_cache=False, seed=32)
+
+
+def test_batch_one_equals_single_row_forward(D):
+    """B = 1 through the batched entry point selects the same masks as the batch-1 call."""
+    d, f, k_in, k_mid = 512, 1536, 200, 500
+    w = layer_weights(d, f, seed=33, layer=0, dtype="bf16")
+    mlp = D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"]))
+    x = ar1_laplace_stream(1, d, seed=5)
+    ws1 = workspace(D.dip_swiglu_mlp_forward_workspace_bytes(mlp, k_in, k_mid))
+    dbg = D.Debug(d, f, k_in, k_mid)
+    y1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    D.dip_swiglu_mlp_forward(mlp, dev_f32(x[0]), k_in, k_mid, None, None, 0.2, y1, dbg, ws1)
+    wsb = workspace(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlp, 1, k_in, k_mid))
+    m1 = torch.empty(1, (d + 31) // 32, dtype=torch.int32, device="cuda")
+    Y = torch.empty(1, d, dtype=torch.float32, device="cuda")
+    D.dip_swiglu_mlp_forward_batched(mlp, dev_f32(x), 1, k_in, k_mid, None, None, 0.2, Y, m1, None, None, wsb)
+    assert np.array_equal(host_u32(m1[0]), host_u32(dbg.mask_in))
+    assert rel_l2(Y[0].cpu().numpy(), y1.cpu().numpy()) <= 1e-5
+
+
+@pytest.mark.parametrize("B", [2, 8])
+def test_config5_phi3_medium_int4_batched(D, B):
+    cfg = CONFIGS[5]
+    run_steps(D, cfg.d_model, cfg.d_ff, "int4", B, cfg.k_in(0.3), cfg.k_mid(0.3), steps=2,
+              use_cache=True, seed=cfg.seed, layer=1)
