@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--cache-frac", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None,
                     help="distinct weight copies (config 2) or stack depth (configs 3, 4)")
+    ap.add_argument("--batch", type=int, default=1, help="rows per step (config 5 only, 1..8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=24)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -117,8 +118,24 @@ def main():
     t_setup = time.perf_counter() - t_setup
 
     # one "pass" = every layer (copy) once = L steps; steps are rounded to whole passes
+    B = a.batch
+    if B > 1:
+        assert a.config == 5 and B <= 8, "--batch applies to config 5 (1..8 rows)"
+        # row b of layer l at step t is its own stream: take B consecutive tokens of the layer's stream
+        Xb = torch.stack([Xd[(torch.arange(n_tok) + 37 * b) % n_tok] for b in range(B)], dim=2).contiguous()
+        Yb = torch.empty(L, B, d, dtype=torch.float32, device="cuda")
+        ws = torch.empty(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[0], B, k_in, k_mid),
+                         dtype=torch.uint8, device="cuda")
+
     def run_pass(t):
-        D.dip_swiglu_mlp_forward_stack(stack, Xd[t % n_tok], d, k_in, k_mid, cfg.gamma, Yd, d, ws)
+        if B == 1:
+            D.dip_swiglu_mlp_forward_stack(stack, Xd[t % n_tok], d, k_in, k_mid, cfg.gamma, Yd, d, ws)
+        else:
+            for l in range(L):
+                D.dip_swiglu_mlp_forward_batched(mlps[l], Xb[t % n_tok, l], B, k_in, k_mid,
+                                                 cins[l] if use_cache else None,
+                                                 cmids[l] if use_cache else None, cfg.gamma, Yb[l],
+                                                 None, None, None, ws)
 
     passes_w = max(1, (a.warmup + L - 1) // L)
     passes = max(1, (a.steps + L - 1) // L)
@@ -136,7 +153,7 @@ def main():
     bytes_of = (lambda e: e // 2 + (e // 128) * 2) if cfg.dtype == "int4" else (lambda e: e * 2)
     ug_bytes = bytes_of(2 * k_in * f)
     dn_bytes = bytes_of(k_mid * d)
-    tokens_per_s = steps / wall if a.config == 2 else passes / wall   # configs 3-5: L layers per token
+    tokens_per_s = (steps / wall if a.config == 2 else passes / wall) * B   # configs 3-5: L layers per token
     out = {
         "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
         "value": tokens_per_s,
@@ -154,7 +171,9 @@ def main():
             "inputs": cfg.inputs, "weights_dtype": cfg.dtype,
             "weight_bytes_resident": int(L * bytes_of(3 * d * f)),
             "gathered_bytes_per_step": gathered,
-            "step": "one token through one MLP layer (4 kernel launches)",
+            "step": "one token through one MLP layer (4 kernel launches)" if B == 1 else
+                    f"{B} rows through one MLP layer (unioned column reads)",
+            "batch": B,
         },
         "end_to_end_GBps": gathered * steps / wall / 1e9,
         "setup_s": t_setup,
