@@ -464,6 +464,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
         block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need);
         const int pre = (int)tile_prefix_eq_gt<ITEMS>(key, T, sh, phase);
         const bool want_words = p.mask_out || p.c_bits;
+        // a wave ballot over slot j is two words of the mask: lane 2j keeps the low word and
+        // lane 2j+1 the high word, stored to LDS once after the loop
+        uint32_t my_word = 0u;
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const int i = j * kSelThreads + tid;
@@ -476,21 +479,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
                 mine = mine || (key[j] == T && eq_before + lanes_below(be) < need);
             }
             const uint64_t bs = __ballot(mine);
-            if (mine) {
-                sel |= 1u << j;
-                const uint32_t pos = gt_before + min(eq_before, need) + lanes_below(bs);
-                if (pos < (uint32_t)p.k) {  // always true; keeps a logic slip from writing out of bounds
-                    if (p.idx_out) p.idx_out[pos] = i;
-                    if (p.val_out) p.val_out[pos] = v[j];
-                }
+            const uint32_t pos = gt_before + min(eq_before, need) + lanes_below(bs);
+            // pos < k always holds; the test keeps a logic slip from writing out of bounds
+            if (mine && pos < (uint32_t)p.k) {
+                if (p.idx_out) p.idx_out[pos] = i;
+                if (p.val_out) p.val_out[pos] = v[j];
             }
-            if (want_words) {
-                // a wave ballot over one slot is two words of the mask
-                const int w0 = j * (kSelThreads / 32) + wave * 2;
-                if (lane == 0) sh.mw[w0] = (uint32_t)bs;
-                if (lane == 32) sh.mw[w0 + 1] = (uint32_t)(bs >> 32);
-            }
+            sel |= mine ? (1u << j) : 0u;
+            my_word = lane == 2 * j ? (uint32_t)bs : my_word;
+            my_word = lane == 2 * j + 1 ? (uint32_t)(bs >> 32) : my_word;
         }
+        if (want_words && lane < 2 * ITEMS)
+            sh.mw[(lane >> 1) * (kSelThreads / 32) + wave * 2 + (lane & 1)] = my_word;
         if (want_words) __syncthreads();
         if (p.mask_out && tid < nwords) p.mask_out[tid] = sh.mw[tid];
     }
