@@ -304,3 +304,71 @@ def mlp_forward_batched(w_ug, w_d, X, k_in: int, k_mid: int,
 def gathered_weight_elements(k_in: int, k_mid: int, d_model: int, d_ff: int) -> int:
     """Weight elements one token must read: two matrices at point 1, one at point 2 (Sec. 4)."""
     return 2 * k_in * d_ff + k_mid * d_model
+
+
+# ---------------------------------------------------------------------------
+# Sec. 3.2: the sibling schemes that prune on (partial) GLU activations
+# ---------------------------------------------------------------------------
+GLU_PRUNING, GATE_PRUNING, UP_PRUNING = "glu", "gate", "up"
+
+
+def gathered_rowdot(w_rows, x: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """(W x)_j for the selected output neurons j, in fp64.
+
+    ``w_rows`` is neuron-major (stored row j = the paper's row j), so removing the
+    rows of W that a mask drops leaves exactly these dot products.
+    """
+    idx = np.asarray(idx, dtype=np.int64)
+    return widen_rows(w_rows, idx) @ np.asarray(x, dtype=F32).astype(F64)
+
+
+def glu_pruning_forward(w_ug, w_d, x, k: int) -> dict:
+    """GLU pruning (Sec. 3.2): W^u x and W^g x are dense; topK(|GLU(x)|) removes columns of W^d."""
+    x = np.asarray(x, dtype=F32)
+    d = n_rows(w_ug)
+    h = glu_from_preacts(gathered_gemv(w_ug, x, np.arange(d)))
+    m, idx = topk(np.abs(h), k)
+    y = gathered_gemv(w_d, h, idx).astype(F32)
+    return {"a": h, "mask": m, "idx": idx, "h_sel": h[idx], "y": y}
+
+
+def partial_pruning_forward(scheme: str, w_dense, w_rows, w_d, x, k: int) -> dict:
+    """Gate pruning and Up pruning (Sec. 3.2).
+
+    gate:  a = sigma(W^g x) dense,  m = topK(|a|),  W^u loses the rows and W^d the columns
+           outside m:  h_j = (W^u x)_j a_j  for j in m.
+    up:    a = W^u x dense,         m = topK(|a|),  W^g and W^d are pruned:
+           h_j = a_j sigma((W^g x)_j)  for j in m.
+    ``w_dense`` is the densely multiplied matrix, feature-major [d][f]; ``w_rows`` the
+    other one, neuron-major [f][d]; ``w_d`` feature-major [f][d].  The partial
+    activation a is rounded to fp32 once; that array is both the selection key and
+    the factor of h.  h is returned compact (one value per selected neuron, ascending).
+    """
+    x = np.asarray(x, dtype=F32)
+    d = n_rows(w_dense)
+    pre = gathered_gemv(w_dense, x, np.arange(d))            # fp64, all f neurons
+    if scheme == GATE_PRUNING:
+        a = silu(pre).astype(F32)
+    elif scheme == UP_PRUNING:
+        a = pre.astype(F32)
+    else:
+        raise ValueError(scheme)
+    m, idx = topk(np.abs(a), k)
+    other = gathered_rowdot(w_rows, x, idx)                  # fp64, k neurons
+    if scheme == GATE_PRUNING:
+        h_sel = (other * a[idx].astype(F64)).astype(F32)
+    else:
+        h_sel = (a[idx].astype(F64) * silu(other)).astype(F32)
+    h = np.zeros(a.shape[0], dtype=F32)
+    h[idx] = h_sel
+    y = gathered_gemv(w_d, h, idx).astype(F32)
+    return {"a": a, "mask": m, "idx": idx, "h_sel": h_sel, "y": y}
+
+
+def sibling_weight_elements(scheme: str, k: int, d_model: int, d_ff: int) -> int:
+    """Weight elements one token reads under a Sec. 3.2 scheme with k kept GLU units."""
+    if scheme == GLU_PRUNING:
+        return 2 * d_model * d_ff + k * d_model
+    if scheme in (GATE_PRUNING, UP_PRUNING):
+        return d_model * d_ff + 2 * k * d_model
+    raise ValueError(scheme)

@@ -14,7 +14,7 @@ from .synth import (  # noqa: F401
     f32_to_bf16_bits,
     gaussian_tokens,
     k_from_ratio,
-    layer_weights,
+    layer_weights, layer_weights_split,
     lru_warm_bits,
     pack_int4_g128,
     studentt_tokens,

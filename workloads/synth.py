@@ -104,6 +104,35 @@ def layer_weights(d_model: int, d_ff: int, seed: int, layer: int = 0,
     raise ValueError(dtype)
 
 
+def layer_weights_split(d_model: int, d_ff: int, seed: int, layer: int = 0,
+                        dtype: str = "f32", std: float = 0.02):
+    """The same three matrices as ``layer_weights``, stored apart for the schemes that
+    multiply one of W^u / W^g densely and gather whole rows of the other.
+
+    Returns a dict with
+      'u', 'g'           : feature-major, shape [d_model][d_ff]   (stored row i = column i)
+      'u_rows', 'g_rows' : neuron-major,  shape [d_ff][d_model]   (stored row j = row j)
+      'd'                : feature-major, shape [d_ff][d_model]
+    in the storage format of ``dtype`` (a 4-bit matrix is quantised per stored row, so its
+    two layouts hold slightly different values).
+    """
+    rng = np.random.default_rng(seed * 1000 + layer)
+    ug = rng.standard_normal((d_model, 2 * d_ff), dtype=np.float32)
+    ug *= np.float32(std)
+    dn = rng.standard_normal((d_ff, d_model), dtype=np.float32)
+    dn *= np.float32(std)
+    mats = {"u": np.ascontiguousarray(ug[:, :d_ff]), "g": np.ascontiguousarray(ug[:, d_ff:]),
+            "u_rows": np.ascontiguousarray(ug[:, :d_ff].T), "g_rows": np.ascontiguousarray(ug[:, d_ff:].T),
+            "d": dn}
+    if dtype == "f32":
+        return mats
+    if dtype == "bf16":
+        return {k: f32_to_bf16_bits(v) for k, v in mats.items()}
+    if dtype == "int4":
+        return {k: pack_int4_g128(v) for k, v in mats.items()}
+    raise ValueError(dtype)
+
+
 # --------------------------------------------------------------------------
 # activations
 # --------------------------------------------------------------------------
