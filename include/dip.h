@@ -124,6 +124,32 @@ typedef struct dip_debug {
     int32_t* idx_mid;   /* k_mid ascending indices (16-byte aligned)                        */
 } dip_debug;
 
+/* The sibling schemes of Sec. 3.2 that prune on a partial activation. */
+typedef enum dip_scheme {
+    DIP_GATE_PRUNING = 1, /* a = SiLU(W^g x) dense; topK(|a|) removes rows of W^u, columns of W^d */
+    DIP_UP_PRUNING = 2    /* a = W^u x dense;       topK(|a|) removes rows of W^g, columns of W^d */
+} dip_scheme;
+
+/* The three matrices of one SwiGLU MLP stored for Gate / Up pruning.  The matrix that is
+ * multiplied densely (W^g for gate pruning, W^u for up pruning) is feature-major like every
+ * other matrix here.  The one whose ROWS the mask removes is NEURON-MAJOR: stored row j is
+ * row j of the paper's matrix, the d_model weights of GLU unit j, so that a kept unit is one
+ * contiguous burst; in its descriptor n_in = d_ff (stored rows) and n_out = d_model
+ * (elements per stored row). */
+typedef struct dip_mlp_split {
+    dip_weight w_dense; /* feature-major, n_in = d_model, n_out = d_ff                      */
+    dip_weight w_rows;  /* neuron-major,  n_in = d_ff,    n_out = d_model                   */
+    dip_weight w_d;     /* feature-major, n_in = d_ff,    n_out = d_model                   */
+} dip_mlp_split;
+
+/* Optional stage outputs of dip_partial_pruning_forward; every member may be NULL. */
+typedef struct dip_partial_debug {
+    float* a;       /* d_ff: the partial activation the mask is taken from                  */
+    uint32_t* mask; /* ceil(d_ff/32) words                                                  */
+    int32_t* idx;   /* k ascending kept GLU units (16-byte aligned)                         */
+    float* h_sel;   /* k values of GLU~(x) at those units (16-byte aligned)                 */
+} dip_partial_debug;
+
 /* (major << 16) | minor. */
 int32_t dip_version(void);
 
@@ -240,6 +266,41 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
                                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * GLU pruning, Sec. 3.2: W^u x and W^g x are dense, m = topK(|GLU(x)|, k) removes columns
+ * of W^d:  y = sum_{i in m} W^d[:, i] GLU(x)_i.  Same matrices, layout and workspace rules
+ * as dip_swiglu_mlp_forward; the point-1 members of dbg must be NULL.
+ */
+size_t dip_glu_pruning_forward_workspace_bytes(const dip_mlp* mlp, int32_t k);
+int32_t dip_glu_pruning_forward(const dip_mlp* mlp, const float* x, int32_t k, float* y_out,
+                                const dip_debug* dbg, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Row-gathered dot products: out[t] = W[idx[t], :] . x  for t < k, fp32 accumulation in a
+ * fixed order -- what is left of W x when a mask removes rows of W (Sec. 3.2, the W^u of
+ * gate pruning).
+ *   w_rows   neuron-major matrix: n_in stored rows of n_out elements (n_out <= DIP_MAX_N)
+ *   x        n_out floats, 16-byte aligned     idx   k ascending stored-row indices
+ *   out      k floats
+ */
+int32_t dip_gathered_rowdot(const dip_weight* w_rows, const float* x, const int32_t* idx, int32_t k,
+                            float* out, void* stream);
+
+/*
+ * Gate pruning and Up pruning, Sec. 3.2, one token through one MLP:
+ *   1. a = SiLU(W^g x)  (gate)   or   a = W^u x  (up)        dense, all d_ff units, fp32
+ *   2. m = topK(|a|, k)                                       lowest index wins ties
+ *   3. h_j = (W^u x)_j a_j  (gate)   or   a_j SiLU((W^g x)_j)  (up)      for j in m only
+ *   4. y = sum_{j in m} W^d[:, j] h_j
+ * The fp32 array a is both the selection key and the factor in step 3.
+ *   x     d_model floats, 16-byte aligned      y_out   d_model floats     1 <= k <= d_ff
+ *   dbg   NULL or stage outputs                ws      *_workspace_bytes() bytes, 256-aligned
+ */
+size_t dip_partial_pruning_forward_workspace_bytes(const dip_mlp_split* mlp, int32_t k);
+int32_t dip_partial_pruning_forward(const dip_mlp_split* mlp, int32_t scheme, const float* x,
+                                    int32_t k, float* y_out, const dip_partial_debug* dbg,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Launch-shape override for the gathered GEMV kernels, for tuning sweeps.  0 restores the
  * built-in choice for that parameter.  Host-side, process-wide, not thread-safe against
  * concurrent launches.
@@ -271,6 +332,9 @@ int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, i
 #define DIP_KERNEL_GEMV_UPGATE 1 /* gathered up/gate GEMV + SwiGLU                          */
 #define DIP_KERNEL_SELECT_MID 2  /* scores + top-K + cache update at pruning point 2       */
 #define DIP_KERNEL_GEMV_DOWN 3   /* gathered down GEMV (also dip_gathered_gemv)             */
+#define DIP_KERNEL_GEMV_DENSE 4  /* dense first product of gate / up pruning                */
+#define DIP_KERNEL_ROWDOT 5      /* row-gathered dot products                               */
+#define DIP_KERNEL_KINDS 6
 int32_t dip_profile_enable(int32_t max_launches);
 int32_t dip_profile_read(int32_t kind, double* total_ms /* host */, int32_t* launches /* host */);
 int32_t dip_profile_disable(void);

@@ -13,5 +13,8 @@ from .libdip import (  # noqa: F401
     dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack,
     dip_swiglu_mlp_forward_workspace_bytes, dip_tune_gemv, dip_version, MlpStack, EXPORTS, META,
     dip_gemv_launch_shape, dip_profile_enable,
+    DIP_GATE_PRUNING, DIP_UP_PRUNING, MlpSplit, PartialDebug, glu_debug, dip_glu_pruning_forward,
+    dip_glu_pruning_forward_workspace_bytes, dip_gathered_rowdot, dip_partial_pruning_forward,
+    dip_partial_pruning_forward_workspace_bytes,
     dip_swiglu_mlp_forward_batched, dip_swiglu_mlp_forward_batched_workspace_bytes, dip_profile_read, dip_profile_disable,
 )

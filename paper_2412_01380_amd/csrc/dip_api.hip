@@ -140,7 +140,7 @@ int32_t validate_mlp(const dip_mlp* mlp, int k_in, int k_mid) {
 
 int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, int k_in, int k_mid,
                     const dip_cache* cin, const dip_cache* cmid, float gamma, float* y,
-                    const dip_debug* dbg, char* ws, hipStream_t stream) {
+                    const dip_debug* dbg, char* ws, hipStream_t stream, bool dense_in = false) {
     int32_t* idx1 = reinterpret_cast<int32_t*>(ws + pl.off_idx1);
     float* val1 = reinterpret_cast<float*>(ws + pl.off_val1);
     float* h = reinterpret_cast<float*>(ws + pl.off_h);
@@ -154,20 +154,27 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     if (dbg && dbg->idx_mid) idx2 = dbg->idx_mid;
     if (dbg && dbg->h) h = dbg->h;
 
-    // point 1: scores, m1, cache update
-    SelectParams s1;
-    std::memset(&s1, 0, sizeof(s1));
-    s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
-    s1.s_out = dbg ? dbg->s_in : nullptr;
-    s1.mask_out = dbg ? dbg->mask_in : nullptr;
-    s1.idx_out = idx1; s1.val_out = val1;
-    if (cin) {
-        s1.score_bits = cin->bits; s1.c_bits = cin->bits; s1.c_stamp = cin->stamp; s1.c_meta = cin->meta;
-        s1.capacity = cin->capacity; s1.policy = cin->policy;
+    int32_t st = DIP_OK;
+    if (dense_in) {
+        // GLU pruning (Sec. 3.2): nothing is pruned at point 1, every stored row in order
+        st = check_hip(launch_zero_u32(cnt_ug, pl.strips_ug + pl.strips_dn, stream), "counter reset");
+        if (st) return st;
+    } else {
+        // point 1: scores, m1, cache update
+        SelectParams s1;
+        std::memset(&s1, 0, sizeof(s1));
+        s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
+        s1.s_out = dbg ? dbg->s_in : nullptr;
+        s1.mask_out = dbg ? dbg->mask_in : nullptr;
+        s1.idx_out = idx1; s1.val_out = val1;
+        if (cin) {
+            s1.score_bits = cin->bits; s1.c_bits = cin->bits; s1.c_stamp = cin->stamp; s1.c_meta = cin->meta;
+            s1.capacity = cin->capacity; s1.policy = cin->policy;
+        }
+        s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
+        st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
+        if (st) return st;
     }
-    s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
-    int32_t st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
-    if (st) return st;
 
     // gathered up/gate GEMV + SwiGLU
     GemvParams g1;
@@ -175,6 +182,7 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes;
     g1.scales = static_cast<const uint16_t*>(mlp->w_ug.scales); g1.scale_stride = mlp->w_ug.n_out / 128; g1.dtype = mlp->w_ug.dtype;
     g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.idx = idx1; g1.val = val1; g1.k = k_in; g1.out = h;
+    if (dense_in) { g1.idx = nullptr; g1.val = x; }
     g1.partial = part_ug; g1.counters = cnt_ug;
     st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
     if (st) return st;
@@ -311,7 +319,7 @@ static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const floa
                                int32_t k_in, int32_t k_mid, const dip_cache* caches_in,
                                const dip_cache* caches_mid, float gamma, float* y_out,
                                int64_t y_stride, const dip_debug* dbg, void* ws, size_t ws_bytes,
-                               void* stream) {
+                               void* stream, bool dense_in = false) {
     if (!mlps) return fail(DIP_ERR_INVALID_ARG, "forward: null mlp descriptor");
     if (n_layers < 1) return fail(DIP_ERR_INVALID_ARG, "forward: n_layers must be >= 1");
     if (!x || !y_out) return fail(DIP_ERR_INVALID_ARG, "forward: null x or y_out");
@@ -338,7 +346,7 @@ static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const floa
         int32_t st = forward_one(&mlps[l], pl, x + (int64_t)l * x_stride, k_in, k_mid,
                                  caches_in ? &caches_in[l] : nullptr,
                                  caches_mid ? &caches_mid[l] : nullptr, gamma,
-                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs);
+                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs, dense_in);
         if (st) return st;
     }
     return DIP_OK;
@@ -497,6 +505,153 @@ int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int3
     return DIP_OK;
 }
 
+// ---- Sec. 3.2 sibling schemes ------------------------------------------------------------------
+int32_t dip_glu_pruning_forward(const dip_mlp* mlp, const float* x, int32_t k, float* y_out,
+                                const dip_debug* dbg, void* ws, size_t ws_bytes, void* stream) {
+    if (!mlp) return fail(DIP_ERR_INVALID_ARG, "dip_glu_pruning_forward: null mlp descriptor");
+    if (dbg && (dbg->s_in || dbg->mask_in || dbg->idx_in))
+        return fail(DIP_ERR_INVALID_ARG, "dip_glu_pruning_forward: there is no pruning point 1 to report");
+    return forward_checked(mlp, 1, x, 0, mlp->w_ug.n_in, k, nullptr, nullptr, 0.f, y_out, 0, dbg, ws,
+                           ws_bytes, stream, true);
+}
+
+size_t dip_glu_pruning_forward_workspace_bytes(const dip_mlp* mlp, int32_t k) {
+    if (!mlp) return 0;
+    return dip_swiglu_mlp_forward_workspace_bytes(mlp, mlp->w_ug.n_in, k);
+}
+
+int32_t dip_gathered_rowdot(const dip_weight* w_rows, const float* x, const int32_t* idx, int32_t k,
+                            float* out, void* stream) {
+    int32_t st = validate_weight(w_rows, "dip_gathered_rowdot");
+    if (st) return st;
+    if (!x || !idx || !out) return fail(DIP_ERR_INVALID_ARG, "dip_gathered_rowdot: null pointer");
+    if (k < 1 || k > w_rows->n_in) return fail(DIP_ERR_INVALID_ARG, "dip_gathered_rowdot: k must be in [1, stored rows]");
+    if (!aligned(x, 16)) return fail(DIP_ERR_UNSUPPORTED, "dip_gathered_rowdot: x must be 16-byte aligned");
+    if (w_rows->n_out > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "dip_gathered_rowdot: rows longer than %d", DIP_MAX_N);
+    RowdotParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.w = w_rows->data; p.row_stride = w_rows->row_stride_bytes;
+    p.scales = static_cast<const uint16_t*>(w_rows->scales); p.scale_stride = w_rows->n_out / 128;
+    p.dtype = w_rows->dtype; p.n_rows = w_rows->n_in; p.n_cols = w_rows->n_out;
+    p.idx = idx; p.k = k; p.x = x; p.out = out;
+    return check_hip(launch_rowdot(p, static_cast<hipStream_t>(stream), DIP_KERNEL_ROWDOT), "dip_gathered_rowdot");
+}
+
+namespace {
+struct PartialPlan {
+    int d, f;
+    GemvShape dense, dn;
+    int strips_dense, strips_dn;
+    size_t off_a, off_idx, off_hsel, off_part_dense, off_part_dn, off_cnt, total;
+};
+PartialPlan plan_partial(const dip_mlp_split* mlp, int k) {
+    PartialPlan pl;
+    pl.d = mlp->w_dense.n_in;
+    pl.f = mlp->w_dense.n_out;
+    pl.dense = choose_gemv_shape(mlp->w_dense.dtype, pl.f, 1, pl.d);
+    pl.dn = choose_gemv_shape(mlp->w_d.dtype, pl.d, 1, k);
+    pl.strips_dense = gemv_strips(pl.dense, mlp->w_dense.dtype, pl.f);
+    pl.strips_dn = gemv_strips(pl.dn, mlp->w_d.dtype, pl.d);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    pl.off_a = take(sizeof(float) * pl.f);
+    pl.off_idx = take(sizeof(int32_t) * k);
+    pl.off_hsel = take(sizeof(float) * k);
+    pl.off_part_dense = take(pl.dense.ksplit > 1 ? sizeof(float) * pl.f * pl.dense.ksplit : 0);
+    pl.off_part_dn = take(pl.dn.ksplit > 1 ? sizeof(float) * pl.d * pl.dn.ksplit : 0);
+    pl.off_cnt = take(sizeof(uint32_t) * (pl.strips_dense + pl.strips_dn));
+    pl.total = o;
+    return pl;
+}
+int32_t validate_split(const dip_mlp_split* mlp, int k) {
+    if (!mlp) return fail(DIP_ERR_INVALID_ARG, "mlp: null descriptor");
+    int32_t st = validate_weight(&mlp->w_dense, "w_dense");
+    if (st) return st;
+    if ((st = validate_weight(&mlp->w_rows, "w_rows"))) return st;
+    if ((st = validate_weight(&mlp->w_d, "w_d"))) return st;
+    const int d = mlp->w_dense.n_in, f = mlp->w_dense.n_out;
+    if (mlp->w_rows.n_in != f || mlp->w_rows.n_out != d)
+        return fail(DIP_ERR_INVALID_ARG, "w_rows must hold d_ff stored rows of d_model elements");
+    if (mlp->w_d.n_in != f || mlp->w_d.n_out != d)
+        return fail(DIP_ERR_INVALID_ARG, "w_d must hold d_ff stored rows of d_model elements");
+    if (d > DIP_MAX_N || f > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "d_model and d_ff must be <= %d", DIP_MAX_N);
+    if (k < 1 || k > f) return fail(DIP_ERR_INVALID_ARG, "k must be in [1, d_ff]");
+    return DIP_OK;
+}
+}  // namespace
+
+size_t dip_partial_pruning_forward_workspace_bytes(const dip_mlp_split* mlp, int32_t k) {
+    if (validate_split(mlp, k)) return 0;
+    return plan_partial(mlp, k).total;
+}
+
+int32_t dip_partial_pruning_forward(const dip_mlp_split* mlp, int32_t scheme, const float* x, int32_t k,
+                                    float* y_out, const dip_partial_debug* dbg, void* ws,
+                                    size_t ws_bytes, void* stream) {
+    int32_t st = validate_split(mlp, k);
+    if (st) return st;
+    if (scheme != DIP_GATE_PRUNING && scheme != DIP_UP_PRUNING)
+        return fail(DIP_ERR_INVALID_ARG, "dip_partial_pruning_forward: scheme must be DIP_GATE_PRUNING or DIP_UP_PRUNING");
+    if (!x || !y_out) return fail(DIP_ERR_INVALID_ARG, "dip_partial_pruning_forward: null x or y_out");
+    if (!aligned(x, 16)) return fail(DIP_ERR_UNSUPPORTED, "dip_partial_pruning_forward: x must be 16-byte aligned");
+    if (dbg && !aligned(dbg->idx, 16))
+        return fail(DIP_ERR_UNSUPPORTED, "dip_partial_pruning_forward: debug index list must be 16-byte aligned");
+    if (dbg && !aligned(dbg->h_sel, 16))
+        return fail(DIP_ERR_UNSUPPORTED, "dip_partial_pruning_forward: debug h_sel must be 16-byte aligned");
+    const PartialPlan pl = plan_partial(mlp, k);
+    if (!ws || ws_bytes < pl.total || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "dip_partial_pruning_forward: workspace must be 256-aligned and >= %zu bytes", pl.total);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    float* a = dbg && dbg->a ? dbg->a : reinterpret_cast<float*>(base + pl.off_a);
+    int32_t* idx = dbg && dbg->idx ? dbg->idx : reinterpret_cast<int32_t*>(base + pl.off_idx);
+    float* hsel = dbg && dbg->h_sel ? dbg->h_sel : reinterpret_cast<float*>(base + pl.off_hsel);
+    uint32_t* cnt_dense = reinterpret_cast<uint32_t*>(base + pl.off_cnt);
+    uint32_t* cnt_dn = cnt_dense + pl.strips_dense;
+
+    st = check_hip(launch_zero_u32(cnt_dense, pl.strips_dense + pl.strips_dn, hs), "counter reset");
+    if (st) return st;
+
+    // a = sigma(W^g x) (gate pruning) or W^u x (up pruning), all d_ff neurons
+    GemvParams g1;
+    std::memset(&g1, 0, sizeof(g1));
+    g1.w = mlp->w_dense.data; g1.row_stride = mlp->w_dense.row_stride_bytes;
+    g1.scales = static_cast<const uint16_t*>(mlp->w_dense.scales); g1.scale_stride = mlp->w_dense.n_out / 128;
+    g1.dtype = mlp->w_dense.dtype; g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 1;
+    g1.idx = nullptr; g1.val = x; g1.k = pl.d; g1.out = a;
+    g1.partial = reinterpret_cast<float*>(base + pl.off_part_dense); g1.counters = cnt_dense;
+    g1.act = scheme == DIP_GATE_PRUNING ? 1 : 0;
+    st = check_hip(launch_gemv(g1, pl.dense, hs, DIP_KERNEL_GEMV_DENSE), "dense GEMV");
+    if (st) return st;
+
+    // m = topK(|a|, k)
+    SelectParams sp;
+    std::memset(&sp, 0, sizeof(sp));
+    sp.v = a; sp.n = pl.f; sp.k = k; sp.idx_out = idx; sp.mask_out = dbg ? dbg->mask : nullptr;
+    st = check_hip(launch_select(sp, hs, DIP_KERNEL_SELECT_MID), "select");
+    if (st) return st;
+
+    // the other pre-activation for the kept neurons only, combined into h
+    RowdotParams rp;
+    std::memset(&rp, 0, sizeof(rp));
+    rp.w = mlp->w_rows.data; rp.row_stride = mlp->w_rows.row_stride_bytes;
+    rp.scales = static_cast<const uint16_t*>(mlp->w_rows.scales); rp.scale_stride = mlp->w_rows.n_out / 128;
+    rp.dtype = mlp->w_rows.dtype; rp.n_rows = pl.f; rp.n_cols = pl.d;
+    rp.idx = idx; rp.k = k; rp.x = x; rp.a = a; rp.mode = scheme == DIP_GATE_PRUNING ? 1 : 2; rp.out = hsel;
+    st = check_hip(launch_rowdot(rp, hs, DIP_KERNEL_ROWDOT), "row-gathered dot products");
+    if (st) return st;
+
+    // y = sum over kept neurons of W^d[:, j] h_j
+    GemvParams g2;
+    std::memset(&g2, 0, sizeof(g2));
+    g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes;
+    g2.scales = static_cast<const uint16_t*>(mlp->w_d.scales); g2.scale_stride = mlp->w_d.n_out / 128;
+    g2.dtype = mlp->w_d.dtype; g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1;
+    g2.idx = idx; g2.val = hsel; g2.k = k; g2.out = y_out;
+    g2.partial = reinterpret_cast<float*>(base + pl.off_part_dn); g2.counters = cnt_dn;
+    return check_hip(launch_gemv(g2, pl.dn, hs, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+}
+
 int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out) {
     int32_t st = validate_weight(w, "dip_gemv_launch_shape");
     if (st) return st;
@@ -540,7 +695,7 @@ int32_t dip_profile_enable(int32_t max_launches) {
 
 int32_t dip_profile_read(int32_t kind, double* total_ms, int32_t* launches) {
     if (!total_ms || !launches) return fail(DIP_ERR_INVALID_ARG, "dip_profile_read: null output");
-    if (kind < 0 || kind > 3) return fail(DIP_ERR_INVALID_ARG, "dip_profile_read: unknown kernel kind");
+    if (kind < 0 || kind >= DIP_KERNEL_KINDS) return fail(DIP_ERR_INVALID_ARG, "dip_profile_read: unknown kernel kind");
     double sum = 0.0;
     int32_t n = 0;
     for (size_t i = 0; i < g_prof.used; ++i) {

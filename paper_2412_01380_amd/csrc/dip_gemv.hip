@@ -139,12 +139,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     const int gid = wave * RPW + sub;
     const int n_full = col_ok ? (ke - kb) / ROWS_PER_ITER : 0;
     const bool vec_ok = p.val != nullptr;      // compact multipliers, 16-byte aligned lists
+    const bool ident = p.idx == nullptr;       // every stored row in order (a dense product)
     int t0 = kb + gid * UNROLL;
 
     int row[UNROLL];
     float xv[UNROLL];
     auto fetch_full = [&](int t) {
-        if (vec_ok) {
+        if (ident) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                row[u] = t + u;
+                xv[u] = p.val[t + u];
+            }
+        } else if (vec_ok) {
             if constexpr (UNROLL % 4 == 0) {
 #pragma unroll
                 for (int u = 0; u < UNROLL; u += 4) {
@@ -219,7 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             row[u] = -1;
             xv[u] = 0.f;
             if (t < ke) {
-                const int r = p.idx[t];
+                const int r = ident ? t : p.idx[t];
                 if ((unsigned)r < (unsigned)p.n_in) {
                     row[u] = r;
                     xv[u] = p.val ? p.val[t] : p.x_full[r];
@@ -335,8 +342,114 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
         __syncthreads();
         if (owner && oseg == 0) p.out[gcol] = red[0][0][ocol] * silu(red[0][1][ocol]);
     } else {
-        if (owner) p.out[gcol] = sum;
+        if (owner) p.out[gcol] = p.act == 1 ? silu(sum) : sum;
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Row-gathered dot products (Sec. 3.2, Gate / Up pruning): the matrix whose rows a mask
+// removes is stored neuron-major, so the selected neuron j is one contiguous row and
+//     out[t] = W[idx[t], :] . x
+// streams k whole rows.  One wavefront takes one row at a time, 16 bytes per lane and up to
+// U loads in flight; x sits in LDS.  The sum runs over this lane's elements in column order,
+// then across lanes in a fixed butterfly: bit-repeatable.
+// ---------------------------------------------------------------------------------------
+constexpr int kRowdotWaves = 8;
+
+template <typename WT, int U>
+__global__ __launch_bounds__(kRowdotWaves * 64) void rowdot_kernel(RowdotParams p, int rows_per_wg) {
+    extern __shared__ float xs[];
+    constexpr int EPL = Elem<WT>::kPerLoad;
+    constexpr int STEP = 64 * EPL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid * 4; i < p.n_cols; i += kRowdotWaves * 64 * 4)
+        *reinterpret_cast<float4*>(xs + i) = *reinterpret_cast<const float4*>(p.x + i);
+    __syncthreads();
+
+    const int t_begin = blockIdx.x * rows_per_wg;
+    const int t_end = min(p.k, t_begin + rows_per_wg);
+    for (int t = t_begin + wave; t < t_end; t += kRowdotWaves) {
+        const int r = p.idx[t];
+        float dot = 0.f;
+        if ((unsigned)r < (unsigned)p.n_rows) {   // the same for every lane of the wavefront
+            const char* row = static_cast<const char*>(p.w) + (size_t)r * (size_t)p.row_stride;
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c0 = lane * EPL; c0 < p.n_cols; c0 += U * STEP) {
+                u32x4 q[U];
+                uint16_t sc[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + u * STEP;
+                    q[u] = u32x4{0u, 0u, 0u, 0u};
+                    sc[u] = 0;
+                    if (c < p.n_cols) {
+                        q[u] = load16(row + (size_t)c * Elem<WT>::kBits / 8);
+                        if constexpr (Elem<WT>::kScaled) sc[u] = p.scales[(size_t)r * p.scale_stride + (c >> 7)];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + u * STEP;
+                    if (c < p.n_cols) {
+                        float f[EPL];
+                        Elem<WT>::widen(q[u], f);
+                        float part[4] = {0.f, 0.f, 0.f, 0.f}, xsum = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; e += 4) {
+                            const float4 xv = *reinterpret_cast<const float4*>(xs + c + e);
+                            part[0] = fmaf(f[e], xv.x, part[0]);
+                            part[1] = fmaf(f[e + 1], xv.y, part[1]);
+                            part[2] = fmaf(f[e + 2], xv.z, part[2]);
+                            part[3] = fmaf(f[e + 3], xv.w, part[3]);
+                            if constexpr (Elem<WT>::kScaled) xsum += (xv.x + xv.y) + (xv.z + xv.w);
+                        }
+                        if constexpr (Elem<WT>::kScaled) {
+                            // codes arrive offset by 8 (see Elem<q4_t>)
+                            const float s = half_bits_to_float(sc[u]);
+                            const float v = ((part[0] + part[1]) + (part[2] + part[3])) - 8.0f * xsum;
+                            acc[u & 3] = fmaf(s, v, acc[u & 3]);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[e] += part[e];
+                        }
+                    }
+                }
+            }
+            dot = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
+        if (lane == 0) {
+            float o = dot;
+            if (p.mode != 0) {
+                const float av = (unsigned)r < (unsigned)p.n_rows ? p.a[r] : 0.f;
+                o = p.mode == 1 ? dot * av : av * silu(dot);
+            }
+            p.out[t] = o;
+        }
+    }
+}
+
+template <typename WT, int U>
+hipError_t launch_rowdot_t(const RowdotParams& p, hipStream_t stream, int pk) {
+    // about a thousand workgroups, every wavefront at least one row
+    int rows_per_wg = (p.k + 1023) / 1024;
+    rows_per_wg = (rows_per_wg + kRowdotWaves - 1) / kRowdotWaves * kRowdotWaves;
+    const int grid = (p.k + rows_per_wg - 1) / rows_per_wg;
+    const size_t lds = sizeof(float) * (size_t)p.n_cols;
+    auto kernel = rowdot_kernel<WT, U>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipEvent_t e0, e1;
+    if (pk >= 0 && prof_next(pk, &e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, e0, e1, 0, p, rows_per_wg);
+    } else {
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, p, rows_per_wg);
+    }
+    return hipGetLastError();
 }
 
 template <typename WT, int LPR, int WAVES, int UNROLL>
@@ -441,6 +554,14 @@ hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t str
     if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream, pk);
     if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
     if (p.dtype == DIP_INT4_G128) return launch_lpr<q4_t>(p, s, stream, pk);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_rowdot(const RowdotParams& p, hipStream_t stream, int prof_kind) {
+    if (p.k <= 0) return hipSuccess;
+    if (p.dtype == DIP_F32) return launch_rowdot_t<float, 8>(p, stream, prof_kind);
+    if (p.dtype == DIP_BF16) return launch_rowdot_t<uint16_t, 8>(p, stream, prof_kind);
+    if (p.dtype == DIP_INT4_G128) return launch_rowdot_t<q4_t, 2>(p, stream, prof_kind);
     return hipErrorInvalidValue;
 }
 

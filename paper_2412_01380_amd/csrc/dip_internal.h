@@ -92,7 +92,7 @@ struct GemvParams {
     int n_in;                 // stored rows
     int n_out;                // elements per row actually produced per segment
     int nseg;                 // 1: plain GEMV;  2: bundled [up ; gate] with SwiGLU epilogue
-    const int32_t* idx;       // k ascending row indices
+    const int32_t* idx;       // k ascending row indices; null: rows 0..k-1 (val must be given)
     const float* val;         // compact: val[t] multiplies row idx[t];  or
     const float* x_full;      // full vector: x_full[idx[t]] multiplies row idx[t] (val == null)
     int k;
@@ -100,7 +100,28 @@ struct GemvParams {
     float* out;               // n_out floats (nseg == 2: the GLU output, n_out = d_ff)
     float* partial;           // [ksplit][nseg][n_out] when ksplit > 1
     uint32_t* counters;       // [strips], zero on entry, when ksplit > 1
+    int act;                  // nseg == 1 only: 0 writes the sums, 1 writes SiLU of the sums
 };
+
+// ---- row-gathered dot products (Sec. 3.2, Gate / Up pruning) ---------------------------------
+struct RowdotParams {
+    const void* w;            // neuron-major: stored row j = row j of the paper's matrix
+    int64_t row_stride;       // bytes
+    const uint16_t* scales;
+    int scale_stride;
+    int dtype;
+    int n_rows;
+    int n_cols;
+    const int32_t* idx;       // k ascending stored-row indices
+    int k;
+    const float* x;           // n_cols
+    const float* a;           // n_rows partial activations, or null when mode == 0
+    int mode;                 // 0: out[t] = w[idx[t]] . x
+                              // 1: out[t] = (w[idx[t]] . x) * a[idx[t]]
+                              // 2: out[t] = a[idx[t]] * SiLU(w[idx[t]] . x)
+    float* out;               // k
+};
+hipError_t launch_rowdot(const RowdotParams& p, hipStream_t stream, int prof_kind);
 
 GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k);
 int gemv_strips(const GemvShape& s, int dtype, int n_out);

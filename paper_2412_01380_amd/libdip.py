@@ -17,6 +17,7 @@ lib_path = os.environ.get("DIP_LIBRARY") or os.path.join(HERE, "lib", "libdip.so
 DIP_OK, DIP_ERR_INVALID_ARG, DIP_ERR_UNSUPPORTED, DIP_ERR_WORKSPACE, DIP_ERR_HIP = range(5)
 DIP_F32, DIP_BF16, DIP_INT4_G128 = 0, 1, 2
 DIP_LRU, DIP_LFU = 0, 1
+DIP_GATE_PRUNING, DIP_UP_PRUNING = 1, 2
 DIP_MAX_N = 32768
 DIP_CACHE_META_WORDS = 8
 META = {"step": 0, "resident": 1, "hits": 2, "inserted": 3, "evicted": 4, "bypassed": 5,
@@ -49,6 +50,14 @@ class _Debug(C.Structure):
     _fields_ = [("s_in", C.c_void_p), ("mask_in", C.c_void_p), ("idx_in", C.c_void_p),
                 ("h", C.c_void_p), ("s_mid", C.c_void_p), ("mask_mid", C.c_void_p),
                 ("idx_mid", C.c_void_p)]
+
+
+class _MlpSplit(C.Structure):
+    _fields_ = [("w_dense", _Weight), ("w_rows", _Weight), ("w_d", _Weight)]
+
+
+class _PartialDebug(C.Structure):
+    _fields_ = [("a", C.c_void_p), ("mask", C.c_void_p), ("idx", C.c_void_p), ("h_sel", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -88,6 +97,17 @@ def _load() -> C.CDLL:
     L.dip_swiglu_mlp_forward_batched.restype = i32
     L.dip_swiglu_mlp_forward_batched.argtypes = [C.POINTER(_Mlp), vp, i32, i32, i32, C.POINTER(_Cache),
                                                  C.POINTER(_Cache), f32, vp, vp, vp, vp, vp, sz, vp]
+    L.dip_glu_pruning_forward_workspace_bytes.restype = sz
+    L.dip_glu_pruning_forward_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32]
+    L.dip_glu_pruning_forward.restype = i32
+    L.dip_glu_pruning_forward.argtypes = [C.POINTER(_Mlp), vp, i32, vp, C.POINTER(_Debug), vp, sz, vp]
+    L.dip_gathered_rowdot.restype = i32
+    L.dip_gathered_rowdot.argtypes = [C.POINTER(_Weight), vp, vp, i32, vp, vp]
+    L.dip_partial_pruning_forward_workspace_bytes.restype = sz
+    L.dip_partial_pruning_forward_workspace_bytes.argtypes = [C.POINTER(_MlpSplit), i32]
+    L.dip_partial_pruning_forward.restype = i32
+    L.dip_partial_pruning_forward.argtypes = [C.POINTER(_MlpSplit), i32, vp, i32, vp,
+                                              C.POINTER(_PartialDebug), vp, sz, vp]
     L.dip_tune_gemv.restype = i32
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
     L.dip_gemv_launch_shape.restype = i32
@@ -107,7 +127,9 @@ EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "
            "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
            "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
-           "dip_swiglu_mlp_forward_batched", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
+           "dip_swiglu_mlp_forward_batched", "dip_glu_pruning_forward_workspace_bytes",
+           "dip_glu_pruning_forward", "dip_gathered_rowdot",
+           "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
            "dip_profile_disable"]
 
 
@@ -220,6 +242,31 @@ class Debug:
                         self.idx_mid.data_ptr())
 
 
+class MlpSplit:
+    """Matrices for gate / up pruning: w_dense feature-major [d_model][d_ff] (W^g for gate
+    pruning, W^u for up pruning), w_rows neuron-major [d_ff][d_model] (the other one of the
+    pair), w_d feature-major [d_ff][d_model]."""
+
+    def __init__(self, w_dense: Weight, w_rows: Weight, w_d: Weight):
+        self.w_dense, self.w_rows, self.w_d = w_dense, w_rows, w_d
+        self.c = _MlpSplit(w_dense.c, w_rows.c, w_d.c)
+        self.d_model = w_dense.c.n_in
+        self.d_ff = w_dense.c.n_out
+
+
+class PartialDebug:
+    """Stage outputs of dip_partial_pruning_forward (device tensors allocated by the caller)."""
+
+    def __init__(self, d_ff: int, k: int, device="cuda"):
+        import torch
+        self.a = torch.empty(d_ff, dtype=torch.float32, device=device)
+        self.mask = torch.empty((d_ff + 31) // 32, dtype=torch.int32, device=device)
+        self.idx = torch.empty(k, dtype=torch.int32, device=device)
+        self.h_sel = torch.empty(k, dtype=torch.float32, device=device)
+        self.c = _PartialDebug(self.a.data_ptr(), self.mask.data_ptr(), self.idx.data_ptr(),
+                               self.h_sel.data_ptr())
+
+
 def dip_version() -> int:
     return lib.dip_version()
 
@@ -309,6 +356,45 @@ def dip_swiglu_mlp_forward_batched(mlp: Mlp, X, batch: int, k_in: int, k_mid: in
         C.byref(cache_mid.c) if cache_mid is not None else None,
         gamma, _ptr(Y, torch.float32), _ptr(mask_in_out, torch.int32), _ptr(h_out, torch.float32),
         _ptr(mask_mid_out, torch.int32), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def dip_glu_pruning_forward_workspace_bytes(mlp: Mlp, k: int) -> int:
+    return lib.dip_glu_pruning_forward_workspace_bytes(C.byref(mlp.c), k)
+
+
+def dip_glu_pruning_forward(mlp: Mlp, x, k: int, y_out, dbg, ws, stream=None) -> None:
+    """dbg: a ctypes _Debug whose point-1 members are NULL (see glu_debug), or None."""
+    import torch
+    _check(lib.dip_glu_pruning_forward(
+        C.byref(mlp.c), _ptr(x, torch.float32), k, _ptr(y_out, torch.float32),
+        C.byref(dbg) if dbg is not None else None, _ptr(ws), ws.numel() * ws.element_size(),
+        _stream(stream)))
+
+
+def glu_debug(h=None, s_mid=None, mask_mid=None, idx_mid=None) -> _Debug:
+    """Debug descriptor for dip_glu_pruning_forward: only the point-2 members exist."""
+    import torch
+    return _Debug(None, None, None, _ptr(h, torch.float32), _ptr(s_mid, torch.float32),
+                  _ptr(mask_mid, torch.int32), _ptr(idx_mid, torch.int32))
+
+
+def dip_gathered_rowdot(w_rows: Weight, x, idx, k: int, out, stream=None) -> None:
+    import torch
+    _check(lib.dip_gathered_rowdot(C.byref(w_rows.c), _ptr(x, torch.float32), _ptr(idx, torch.int32),
+                                   k, _ptr(out, torch.float32), _stream(stream)))
+
+
+def dip_partial_pruning_forward_workspace_bytes(mlp: MlpSplit, k: int) -> int:
+    return lib.dip_partial_pruning_forward_workspace_bytes(C.byref(mlp.c), k)
+
+
+def dip_partial_pruning_forward(mlp: MlpSplit, scheme: int, x, k: int, y_out,
+                                dbg: Optional[PartialDebug], ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_partial_pruning_forward(
+        C.byref(mlp.c), scheme, _ptr(x, torch.float32), k, _ptr(y_out, torch.float32),
+        C.byref(dbg.c) if dbg is not None else None, _ptr(ws), ws.numel() * ws.element_size(),
+        _stream(stream)))
 
 
 def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:
