@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None,
                     help="distinct weight copies (config 2) or stack depth (configs 3, 4)")
     ap.add_argument("--batch", type=int, default=1, help="rows per step (config 5 only, 1..8)")
+    ap.add_argument("--scheme", default="dip", choices=("dip", "glu", "gate", "up"),
+                    help="dip: the headline path; glu / gate / up: the sibling schemes that prune on "
+                         "(partial) GLU activations, k = keep ratio of d_ff, no cache")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=24)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -60,6 +63,117 @@ def measured_traffic(workload: str, ratio: float, shape) -> "int | None":
     return None
 
 
+def bench_scheme(a):
+    """One token through one layer under GLU, Gate or Up pruning; same JSON fields as the headline."""
+    import numpy as np
+    import torch
+
+    import paper_2412_01380_amd as D
+    from workloads import CONFIGS, layer_weights, layer_weights_split
+
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[a.config]
+    r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3, 5: 0.3}[a.config]
+    d, f = cfg.d_model, cfg.d_ff
+    k = cfg.k_mid(r)
+    L = a.layers if a.layers is not None else 8
+    n_tok = cfg.n_tokens
+    mk = lambda t: (D.Weight(torch.from_numpy(t[0]).cuda(), torch.from_numpy(t[1]).cuda())
+                    if isinstance(t, tuple) else D.Weight(torch.from_numpy(t.view(np.int16)).cuda()))
+    mlps, host0 = [], None
+    for l in range(L):
+        if a.scheme == "glu":
+            w = layer_weights(d, f, cfg.seed, l, cfg.dtype)
+            mlps.append(D.Mlp(mk(w["ug"]), mk(w["d"])))
+        else:
+            w = layer_weights_split(d, f, cfg.seed, l, cfg.dtype)
+            dense, rows = ("g", "u_rows") if a.scheme == "gate" else ("u", "g_rows")
+            w = {"dense": w[dense], "rows": w[rows], "d": w["d"]}
+            mlps.append(D.MlpSplit(mk(w["dense"]), mk(w["rows"]), mk(w["d"])))
+        if l == 0:
+            host0 = w
+    X = np.stack([cfg.tokens(layer=l, n_tokens=n_tok) for l in range(L)], axis=1)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.empty(L, d, dtype=torch.float32, device="cuda")
+    if a.scheme == "glu":
+        ws = torch.empty(D.dip_glu_pruning_forward_workspace_bytes(mlps[0], k), dtype=torch.uint8, device="cuda")
+        step = lambda t, l: D.dip_glu_pruning_forward(mlps[l], Xd[t % n_tok, l], k, Yd[l], None, ws)
+    else:
+        code = D.DIP_GATE_PRUNING if a.scheme == "gate" else D.DIP_UP_PRUNING
+        ws = torch.empty(D.dip_partial_pruning_forward_workspace_bytes(mlps[0], k), dtype=torch.uint8, device="cuda")
+        step = lambda t, l: D.dip_partial_pruning_forward(mlps[l], code, Xd[t % n_tok, l], k, Yd[l], None, ws)
+
+    def run_pass(t):
+        for l in range(L):
+            step(t, l)
+
+    passes_w = max(1, (a.warmup + L - 1) // L)
+    passes = max(1, (a.steps + L - 1) // L)
+    steps = passes * L
+    for t in range(passes_w):
+        run_pass(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(passes):
+        run_pass(passes_w + t)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    bytes_of = (lambda e: e // 2 + (e // 128) * 2) if cfg.dtype == "int4" else (lambda e: e * 2)
+    dense_bytes = bytes_of((2 if a.scheme == "glu" else 1) * d * f)
+    rows_bytes = 0 if a.scheme == "glu" else bytes_of(k * d)
+    down_bytes = bytes_of(k * d)
+    total = dense_bytes + rows_bytes + down_bytes
+    out = {
+        "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
+        "value": steps / wall, "unit": "layer-tokens/s", "n_gpus": 1, "steps": steps,
+        "warmup": passes_w * L, "ms_per_step": wall / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{a.scheme} pruning (Sec. 3.2) on the MLP shape of BASELINE configs[{a.config - 1}]: "
+                               f"{cfg.name}, d_model={d}, d_ff={f}, {cfg.dtype} weights, batch 1, k={k} of d_ff kept, "
+                               f"{L} distinct weight copies visited round-robin",
+                   "inputs": cfg.inputs, "weights_dtype": cfg.dtype, "weight_bytes_per_step": total},
+        "end_to_end_GBps": total * steps / wall / 1e9,
+    }
+    kinds = {"select_in": 0, "gemv_upgate": 1, "select_mid": 2, "gemv_down": 3, "gemv_dense": 4, "rowdot": 5}
+    n_prof = min(passes, max(1, 1024 // L))
+    D.dip_profile_enable(5 * L * n_prof + 16)
+    for t in range(n_prof):
+        run_pass(passes_w + passes + t)
+    torch.cuda.synchronize()
+    prof = {kname: D.dip_profile_read(i) for kname, i in kinds.items()}
+    D.dip_profile_disable()
+    out["kernels_us"] = {kname: v[0] / v[1] * 1e3 for kname, v in prof.items() if v[1]}
+    main_kind, main_bytes = ("gemv_upgate", dense_bytes) if a.scheme == "glu" else ("gemv_dense", dense_bytes)
+    ms, n = prof[main_kind]
+    ach = main_bytes / (ms / n * 1e-3) / 1e9
+    out["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                       "kernel": "gemv_kernel (dense first product)", "algorithmic_bytes_per_launch": main_bytes,
+                       "avg_launch_us": ms / n * 1e3, "launches": n}
+    if prof["rowdot"][1]:
+        ms, n = prof["rowdot"]
+        out["roofline_rowdot"] = {"achieved": rows_bytes / (ms / n * 1e-3) / 1e9,
+                                  "algorithmic_bytes_per_launch": rows_bytes, "avg_launch_us": ms / n * 1e3}
+    ms, n = prof["gemv_down"]
+    out["roofline_down"] = {"achieved": down_bytes / (ms / n * 1e-3) / 1e9,
+                            "algorithmic_bytes_per_launch": down_bytes, "avg_launch_us": ms / n * 1e3}
+    if not a.no_cpu_baseline:
+        from oracle import dip_oracle as O
+        nt = a.cpu_sample_tokens
+        c0, w0t = time.process_time(), time.perf_counter()
+        for t in range(nt):
+            if a.scheme == "glu":
+                O.glu_pruning_forward(host0["ug"], host0["d"], X[t % n_tok, 0], k)
+            else:
+                O.partial_pruning_forward(a.scheme, host0["dense"], host0["rows"], host0["d"], X[t % n_tok, 0], k)
+        wall_o, cpu_o = time.perf_counter() - w0t, time.process_time() - c0
+        out["cpu_baseline"] = {"value": nt / wall_o, "unit": out["unit"],
+                               "cores": max(1, int(round(cpu_o / wall_o))), "kind": "oracle",
+                               "sample": f"{nt} tokens through layer 0 of the same workload ({wall_o:.1f} s wall)"}
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -75,6 +189,8 @@ def main():
     from workloads import CONFIGS, layer_weights
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if a.scheme != "dip":
+        return bench_scheme(a)
     torch.cuda.set_device(0)
     cfg = CONFIGS[a.config]
     r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3, 5: 0.3}[a.config]

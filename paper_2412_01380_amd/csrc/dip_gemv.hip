@@ -350,94 +350,150 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 // Row-gathered dot products (Sec. 3.2, Gate / Up pruning): the matrix whose rows a mask
 // removes is stored neuron-major, so the selected neuron j is one contiguous row and
 //     out[t] = W[idx[t], :] . x
-// streams k whole rows.  One wavefront takes one row at a time, 16 bytes per lane and up to
-// U loads in flight; x sits in LDS.  The sum runs over this lane's elements in column order,
-// then across lanes in a fixed butterfly: bit-repeatable.
+// streams k whole rows.  One wavefront takes one row at a time, 16 bytes per lane.  A row is
+// cut into chunks of P loads per lane (one chunk when the row fits); the loads of the next
+// chunk are issued into a second set of registers before the current chunk is multiplied,
+// so a wavefront always has one to two chunks outstanding.  The steady-state step has no
+// lane-dependent branch -- columns past the end of a row are re-read from its last 16
+// bytes and dropped by a select -- which lets the compiler wait for exactly the older
+// chunk.  x sits in LDS, laid out in planes of 64 x 16 bytes so that the lanes of a
+// wavefront read consecutive 16-byte pieces.  The sum runs over this lane's elements in
+// column order, then across lanes in a fixed butterfly: bit-repeatable.
 // ---------------------------------------------------------------------------------------
-constexpr int kRowdotWaves = 8;
+constexpr int kRowdotWaves = 4;
 
-template <typename WT, int U>
-__global__ __launch_bounds__(kRowdotWaves * 64) void rowdot_kernel(RowdotParams p, int rows_per_wg) {
-    extern __shared__ float xs[];
+template <typename WT, int P, bool SINGLE>
+__global__ __launch_bounds__(kRowdotWaves * 64) void rowdot_kernel(RowdotParams p, int rows_per_wg, int nchunks) {
+    extern __shared__ __align__(16) float xs[];
     constexpr int EPL = Elem<WT>::kPerLoad;
+    constexpr int PLANES = EPL / 4;          // 16-byte pieces of x per weight load
     constexpr int STEP = 64 * EPL;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid * 4; i < p.n_cols; i += kRowdotWaves * 64 * 4)
-        *reinterpret_cast<float4*>(xs + i) = *reinterpret_cast<const float4*>(p.x + i);
-    __syncthreads();
-
+    constexpr int CHUNK = P * STEP;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t_begin = blockIdx.x * rows_per_wg;
     const int t_end = min(p.k, t_begin + rows_per_wg);
-    for (int t = t_begin + wave; t < t_end; t += kRowdotWaves) {
-        const int r = p.idx[t];
-        float dot = 0.f;
-        if ((unsigned)r < (unsigned)p.n_rows) {   // the same for every lane of the wavefront
-            const char* row = static_cast<const char*>(p.w) + (size_t)r * (size_t)p.row_stride;
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int c0 = lane * EPL; c0 < p.n_cols; c0 += U * STEP) {
-                u32x4 q[U];
-                uint16_t sc[U];
+
+    // element j of x: load group g = j / EPL (one lane's 16 bytes of weights), piece h of it
+    for (int j = tid * 4; j < p.n_cols; j += kRowdotWaves * 64 * 4) {
+        const int g = j / EPL, h = (j % EPL) / 4;
+        *reinterpret_cast<float4*>(xs + ((g >> 6) * PLANES + h) * 256 + (g & 63) * 4) =
+            *reinterpret_cast<const float4*>(p.x + j);
+    }
+    __syncthreads();
+
+    // This wavefront's rows: list positions t0, t0 + 4, ... (at most 64 of them: lane i holds
+    // the index and the partial activation of the i-th, fetched once, handed out with
+    // readlane so that everything that steers the loop sits in scalar registers).
+    // A unit is one chunk of one row.
+    const int t0 = t_begin + wave;
+    if (t0 >= t_end) return;
+    const int n_rows_w = (t_end - t0 + kRowdotWaves - 1) / kRowdotWaves;
+    const int n_units = SINGLE ? n_rows_w : n_rows_w * nchunks;
+    const int last_col = p.n_cols - EPL;
+    int my_r = 0;
+    float my_av = 0.f;
+    bool my_ok = false;
+    if (lane < n_rows_w) {
+        my_r = p.idx[t0 + kRowdotWaves * lane];
+        my_ok = (unsigned)my_r < (unsigned)p.n_rows;   // a row outside the matrix contributes nothing
+        if (!my_ok) my_r = 0;
+        if (p.a) my_av = p.a[my_r];
+    }
+    const uint64_t ok_rows = __ballot(my_ok);
+
+    struct Buf {
+        u32x4 q[P];
+        uint16_t sc[P];
+    };
+    auto issue = [&](int u, Buf& b) {
+        const int i = SINGLE ? u : u / nchunks;
+        const int c0 = SINGLE ? 0 : (u - i * nchunks) * CHUNK;
+        const int r = __builtin_amdgcn_readlane(my_r, i);
+        const char* row = static_cast<const char*>(p.w) + (size_t)r * (size_t)p.row_stride;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int c = c0 + u * STEP;
-                    q[u] = u32x4{0u, 0u, 0u, 0u};
-                    sc[u] = 0;
-                    if (c < p.n_cols) {
-                        q[u] = load16(row + (size_t)c * Elem<WT>::kBits / 8);
-                        if constexpr (Elem<WT>::kScaled) sc[u] = p.scales[(size_t)r * p.scale_stride + (c >> 7)];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int c = c0 + u * STEP;
-                    if (c < p.n_cols) {
-                        float f[EPL];
-                        Elem<WT>::widen(q[u], f);
-                        float part[4] = {0.f, 0.f, 0.f, 0.f}, xsum = 0.f;
-#pragma unroll
-                        for (int e = 0; e < EPL; e += 4) {
-                            const float4 xv = *reinterpret_cast<const float4*>(xs + c + e);
-                            part[0] = fmaf(f[e], xv.x, part[0]);
-                            part[1] = fmaf(f[e + 1], xv.y, part[1]);
-                            part[2] = fmaf(f[e + 2], xv.z, part[2]);
-                            part[3] = fmaf(f[e + 3], xv.w, part[3]);
-                            if constexpr (Elem<WT>::kScaled) xsum += (xv.x + xv.y) + (xv.z + xv.w);
-                        }
-                        if constexpr (Elem<WT>::kScaled) {
-                            // codes arrive offset by 8 (see Elem<q4_t>)
-                            const float s = half_bits_to_float(sc[u]);
-                            const float v = ((part[0] + part[1]) + (part[2] + part[3])) - 8.0f * xsum;
-                            acc[u & 3] = fmaf(s, v, acc[u & 3]);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[e] += part[e];
-                        }
-                    }
-                }
-            }
-            dot = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        for (int v = 0; v < P; ++v) {
+            const int c = min(c0 + v * STEP + lane * EPL, last_col);
+            b.q[v] = load16(row + (size_t)c * Elem<WT>::kBits / 8);
+            b.sc[v] = 0;
+            if constexpr (Elem<WT>::kScaled) b.sc[v] = p.scales[(size_t)r * p.scale_stride + (c >> 7)];
         }
+    };
+    float dot = 0.f;
+    auto consume = [&](int u, const Buf& b) {
+        const int i = SINGLE ? u : u / nchunks;
+        const int cc = SINGLE ? 0 : u - i * nchunks;
+        const int c0 = cc * CHUNK;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
-        if (lane == 0) {
-            float o = dot;
-            if (p.mode != 0) {
-                const float av = (unsigned)r < (unsigned)p.n_rows ? p.a[r] : 0.f;
-                o = p.mode == 1 ? dot * av : av * silu(dot);
+        for (int v = 0; v < P; ++v) {
+            const int craw = c0 + v * STEP + lane * EPL;
+            const int c = min(craw, last_col);
+            const int g = c / EPL;
+            const float* xp = xs + (g >> 6) * (PLANES * 256) + (g & 63) * 4;
+            float f[EPL];
+            Elem<WT>::widen(b.q[v], f);
+            float part[4] = {0.f, 0.f, 0.f, 0.f}, xsum = 0.f;
+#pragma unroll
+            for (int h = 0; h < PLANES; ++h) {
+                const float4 xv = *reinterpret_cast<const float4*>(xp + h * 256);
+                part[0] = fmaf(f[4 * h], xv.x, part[0]);
+                part[1] = fmaf(f[4 * h + 1], xv.y, part[1]);
+                part[2] = fmaf(f[4 * h + 2], xv.z, part[2]);
+                part[3] = fmaf(f[4 * h + 3], xv.w, part[3]);
+                if constexpr (Elem<WT>::kScaled) xsum += (xv.x + xv.y) + (xv.z + xv.w);
             }
-            p.out[t] = o;
+            const bool live = craw < p.n_cols;
+            if constexpr (Elem<WT>::kScaled) {
+                // codes arrive offset by 8 (see Elem<q4_t>)
+                const float sv = half_bits_to_float(b.sc[v]);
+                const float val = ((part[0] + part[1]) + (part[2] + part[3])) - 8.0f * xsum;
+                acc[v & 3] += live ? sv * val : 0.f;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += live ? part[e] : 0.f;
+            }
         }
+        dot += (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        if (!SINGLE && cc != nchunks - 1) return;
+        // the last chunk of row i has been added
+        float total = dot;
+        dot = 0.f;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off);
+        const float av = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_av), i));
+        float o = total;
+        if (p.mode == 1) o = total * av;
+        if (p.mode == 2) o = av * silu(total);
+        if (!((ok_rows >> i) & 1ull)) o = 0.f;
+        if (lane == 0) p.out[t0 + kRowdotWaves * i] = o;
+    };
+
+    Buf A, B;
+    issue(0, A);
+    int u = 0;
+    while (true) {
+        if (u + 1 == n_units) { consume(u, A); break; }
+        issue(u + 1, B);
+        consume(u, A);
+        ++u;
+        if (u + 1 == n_units) { consume(u, B); break; }
+        issue(u + 1, A);
+        consume(u, B);
+        ++u;
     }
 }
 
-template <typename WT, int U>
-hipError_t launch_rowdot_t(const RowdotParams& p, hipStream_t stream, int pk) {
-    // about a thousand workgroups, every wavefront at least one row
-    int rows_per_wg = (p.k + 1023) / 1024;
+template <typename WT, int P, bool SINGLE>
+hipError_t launch_rowdot_p(const RowdotParams& p, int nchunks, hipStream_t stream, int pk) {
+    // one resident generation of workgroups (two per compute unit), whole rows per wavefront
+    int rows_per_wg = (p.k + 511) / 512;
     rows_per_wg = (rows_per_wg + kRowdotWaves - 1) / kRowdotWaves * kRowdotWaves;
+    if (rows_per_wg > 64 * kRowdotWaves) rows_per_wg = 64 * kRowdotWaves;   // one row per lane of a wavefront at most
     const int grid = (p.k + rows_per_wg - 1) / rows_per_wg;
-    const size_t lds = sizeof(float) * (size_t)p.n_cols;
-    auto kernel = rowdot_kernel<WT, U>;
+    constexpr int STEP = 64 * Elem<WT>::kPerLoad;
+    const size_t lds = sizeof(float) * (size_t)((p.n_cols + STEP - 1) / STEP) * STEP;
+    auto kernel = rowdot_kernel<WT, P, SINGLE>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -445,11 +501,27 @@ hipError_t launch_rowdot_t(const RowdotParams& p, hipStream_t stream, int pk) {
     }
     hipEvent_t e0, e1;
     if (pk >= 0 && prof_next(pk, &e0, &e1)) {
-        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, e0, e1, 0, p, rows_per_wg);
+        hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, e0, e1, 0, p,
+                              rows_per_wg, nchunks);
     } else {
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, p, rows_per_wg);
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kRowdotWaves * 64), lds, stream, p, rows_per_wg, nchunks);
     }
     return hipGetLastError();
+}
+
+template <typename WT>
+hipError_t launch_rowdot_t(const RowdotParams& p, hipStream_t stream, int pk) {
+    const int step = 64 * Elem<WT>::kPerLoad;
+    const int passes = (p.n_cols + step - 1) / step;
+    // whole row in flight, twice (x then stays in registers) ...
+    if (passes <= 2) return launch_rowdot_p<WT, 2, true>(p, 1, stream, pk);
+    if (passes <= 4) return launch_rowdot_p<WT, 4, true>(p, 1, stream, pk);
+    if (passes <= 6) return launch_rowdot_p<WT, 6, true>(p, 1, stream, pk);
+    if (passes <= 8) return launch_rowdot_p<WT, 8, true>(p, 1, stream, pk);
+    // ... or in two or more chunks when that would not fit the register file
+    if (passes <= 10) return launch_rowdot_p<WT, 5, false>(p, 2, stream, pk);
+    if (passes <= 12) return launch_rowdot_p<WT, 6, false>(p, 2, stream, pk);
+    return launch_rowdot_p<WT, 8, false>(p, (passes + 7) / 8, stream, pk);
 }
 
 template <typename WT, int LPR, int WAVES, int UNROLL>
@@ -559,9 +631,9 @@ hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t str
 
 hipError_t launch_rowdot(const RowdotParams& p, hipStream_t stream, int prof_kind) {
     if (p.k <= 0) return hipSuccess;
-    if (p.dtype == DIP_F32) return launch_rowdot_t<float, 8>(p, stream, prof_kind);
-    if (p.dtype == DIP_BF16) return launch_rowdot_t<uint16_t, 8>(p, stream, prof_kind);
-    if (p.dtype == DIP_INT4_G128) return launch_rowdot_t<q4_t, 2>(p, stream, prof_kind);
+    if (p.dtype == DIP_F32) return launch_rowdot_t<float>(p, stream, prof_kind);
+    if (p.dtype == DIP_BF16) return launch_rowdot_t<uint16_t>(p, stream, prof_kind);
+    if (p.dtype == DIP_INT4_G128) return launch_rowdot_t<q4_t>(p, stream, prof_kind);
     return hipErrorInvalidValue;
 }
 
