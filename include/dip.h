@@ -268,7 +268,7 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
 /*
  * GLU pruning, Sec. 3.2: W^u x and W^g x are dense, m = topK(|GLU(x)|, k) removes columns
  * of W^d:  y = sum_{i in m} W^d[:, i] GLU(x)_i.  Same matrices, layout and workspace rules
- * as dip_swiglu_mlp_forward; the point-1 members of dbg must be NULL.
+ * as dip_swiglu_mlp_forward; x must be 16-byte aligned; the point-1 members of dbg must be NULL.
  */
 size_t dip_glu_pruning_forward_workspace_bytes(const dip_mlp* mlp, int32_t k);
 int32_t dip_glu_pruning_forward(const dip_mlp* mlp, const float* x, int32_t k, float* y_out,

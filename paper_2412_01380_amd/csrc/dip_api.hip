@@ -278,6 +278,7 @@ size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k) {
     const GemvShape s = choose_gemv_shape(w->dtype, w->n_out, 1, k);
     const int strips = gemv_strips(s, w->dtype, w->n_out);
     size_t bytes = align_up(sizeof(uint32_t) * strips, 256);
+    bytes += 2 * align_up(sizeof(float) * (size_t)k, 256);   // aligned copies of idx and x[idx]
     if (s.ksplit > 1) bytes += align_up(sizeof(float) * (size_t)w->n_out * s.ksplit, 256);
     return bytes;
 }
@@ -296,16 +297,24 @@ int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* id
     hipStream_t hs = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(ws);
     uint32_t* counters = reinterpret_cast<uint32_t*>(base);
-    float* partial = reinterpret_cast<float*>(base + align_up(sizeof(uint32_t) * strips, 256));
+    size_t o = align_up(sizeof(uint32_t) * strips, 256);
+    int32_t* idx_copy = reinterpret_cast<int32_t*>(base + o);
+    o += align_up(sizeof(float) * (size_t)k, 256);
+    float* val = reinterpret_cast<float*>(base + o);
+    o += align_up(sizeof(float) * (size_t)k, 256);
+    float* partial = reinterpret_cast<float*>(base + o);
     if (s.ksplit > 1) {
         st = check_hip(launch_zero_u32(counters, strips, hs), "dip_gathered_gemv: counter reset");
         if (st) return st;
     }
+    // the kernel reads (index, multiplier) pairs as aligned vectors
+    st = check_hip(launch_gather(x, idx, k, w->n_in, val, idx_copy, hs), "dip_gathered_gemv: gather");
+    if (st) return st;
     GemvParams p;
     std::memset(&p, 0, sizeof(p));
     p.w = w->data; p.row_stride = w->row_stride_bytes; p.dtype = w->dtype;
     p.scales = static_cast<const uint16_t*>(w->scales); p.scale_stride = w->n_out / 128; p.n_in = w->n_in; p.n_out = w->n_out;
-    p.nseg = 1; p.idx = idx; p.val = nullptr; p.x_full = x; p.k = k; p.out = y_out;
+    p.nseg = 1; p.idx = idx_copy; p.val = val; p.k = k; p.out = y_out;
     p.partial = partial; p.counters = counters;
     return check_hip(launch_gemv(p, s, hs, DIP_KERNEL_GEMV_DOWN), "dip_gathered_gemv");
 }
@@ -388,12 +397,13 @@ BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     pl.off_m1 = take(sizeof(uint32_t) * B * pl.wd);
     pl.off_u1 = take(sizeof(uint32_t) * pl.wd);
-    pl.off_idx1 = take(sizeof(int32_t) * pl.k1max);
-    pl.off_val1 = take(sizeof(float) * (size_t)pl.k1max * B);
+    // index and multiplier lists carry 8 spare entries: the product reads whole vectors
+    pl.off_idx1 = take(sizeof(int32_t) * (pl.k1max + 8));
+    pl.off_val1 = take(sizeof(float) * (size_t)(pl.k1max + 8) * B);
     pl.off_m2 = take(sizeof(uint32_t) * B * pl.wf);
     pl.off_u2 = take(sizeof(uint32_t) * pl.wf);
-    pl.off_idx2 = take(sizeof(int32_t) * pl.k2max);
-    pl.off_val2 = take(sizeof(float) * (size_t)pl.k2max * B);
+    pl.off_idx2 = take(sizeof(int32_t) * (pl.k2max + 8));
+    pl.off_val2 = take(sizeof(float) * (size_t)(pl.k2max + 8) * B);
     pl.off_cnt = take(sizeof(uint32_t) * 2);
     pl.off_h = take(sizeof(float) * (size_t)B * pl.f);
     const size_t p1 = sizeof(float) * (size_t)pl.g1 * B * 2 * pl.f;
@@ -511,6 +521,7 @@ int32_t dip_glu_pruning_forward(const dip_mlp* mlp, const float* x, int32_t k, f
     if (!mlp) return fail(DIP_ERR_INVALID_ARG, "dip_glu_pruning_forward: null mlp descriptor");
     if (dbg && (dbg->s_in || dbg->mask_in || dbg->idx_in))
         return fail(DIP_ERR_INVALID_ARG, "dip_glu_pruning_forward: there is no pruning point 1 to report");
+    if (!aligned(x, 16)) return fail(DIP_ERR_UNSUPPORTED, "dip_glu_pruning_forward: x must be 16-byte aligned");
     return forward_checked(mlp, 1, x, 0, mlp->w_ug.n_in, k, nullptr, nullptr, 0.f, y_out, 0, dbg, ws,
                            ws_bytes, stream, true);
 }

@@ -109,8 +109,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     const int sub = lane / LPR, l = lane % LPR;
     const int strip = blockIdx.x;
     const int g = blockIdx.y, G = gridDim.y;
-    const int col = strip * SC + l * EPL;
-    const bool col_ok = col < p.n_out;
+    const int col_raw = strip * SC + l * EPL;
+    const bool col_ok = col_raw < p.n_out;
+    // lanes past the right edge of a ragged last strip re-read its last 16 bytes; they own no output
+    const int col = col_ok ? col_raw : p.n_out - EPL;
 
     // this workgroup's share of the selected rows
     const int kb = min(p.k, g * p.rows_per_split);   // rows_per_split is a multiple of 8
@@ -137,50 +139,44 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     // predicates; the pairs of the next iteration are requested right after this
     // iteration's weight loads so that their latency hides behind the weights.
     const int gid = wave * RPW + sub;
-    const int n_full = col_ok ? (ke - kb) / ROWS_PER_ITER : 0;
-    const bool vec_ok = p.val != nullptr;      // compact multipliers, 16-byte aligned lists
+    const int n_full = (ke - kb) / ROWS_PER_ITER;   // the same for every lane
     const bool ident = p.idx == nullptr;       // every stored row in order (a dense product)
     int t0 = kb + gid * UNROLL;
 
+    auto fetch_pairs = [&](int t, int (&row)[UNROLL], float (&xv)[UNROLL]) {
+        if constexpr (UNROLL % 4 == 0) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; u += 4) {
+                const float4 x4 = *reinterpret_cast<const float4*>(p.val + t + u);
+                int4 r4 = make_int4(t + u, t + u + 1, t + u + 2, t + u + 3);
+                if (!ident) r4 = *reinterpret_cast<const int4*>(p.idx + t + u);
+                row[u] = r4.x; row[u + 1] = r4.y; row[u + 2] = r4.z; row[u + 3] = r4.w;
+                xv[u] = x4.x; xv[u + 1] = x4.y; xv[u + 2] = x4.z; xv[u + 3] = x4.w;
+            }
+        } else if constexpr (UNROLL == 2) {
+            const float2 x2 = *reinterpret_cast<const float2*>(p.val + t);
+            int2 r2 = make_int2(t, t + 1);
+            if (!ident) r2 = *reinterpret_cast<const int2*>(p.idx + t);
+            row[0] = r2.x; row[1] = r2.y;
+            xv[0] = x2.x; xv[1] = x2.y;
+        } else {
+            xv[0] = p.val[t];
+            row[0] = t;
+            if (!ident) row[0] = p.idx[t];
+        }
+    };
+    // an index outside the matrix reads row 0 with multiplier 0
+    auto settle_pairs = [&](int (&row)[UNROLL], float (&xv)[UNROLL]) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const bool inside = (unsigned)row[u] < (unsigned)p.n_in;
+            row[u] = inside ? row[u] : 0;
+            xv[u] = inside ? xv[u] : 0.f;
+        }
+    };
     int row[UNROLL];
     float xv[UNROLL];
-    auto fetch_full = [&](int t) {
-        if (ident) {
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                row[u] = t + u;
-                xv[u] = p.val[t + u];
-            }
-        } else if (vec_ok) {
-            if constexpr (UNROLL % 4 == 0) {
-#pragma unroll
-                for (int u = 0; u < UNROLL; u += 4) {
-                    const int4 r4 = *reinterpret_cast<const int4*>(p.idx + t + u);
-                    const float4 x4 = *reinterpret_cast<const float4*>(p.val + t + u);
-                    row[u] = r4.x; row[u + 1] = r4.y; row[u + 2] = r4.z; row[u + 3] = r4.w;
-                    xv[u] = x4.x; xv[u + 1] = x4.y; xv[u + 2] = x4.z; xv[u + 3] = x4.w;
-                }
-            } else if constexpr (UNROLL == 2) {
-                const int2 r2 = *reinterpret_cast<const int2*>(p.idx + t);
-                const float2 x2 = *reinterpret_cast<const float2*>(p.val + t);
-                row[0] = r2.x; row[1] = r2.y;
-                xv[0] = x2.x; xv[1] = x2.y;
-            } else {
-                row[0] = p.idx[t];
-                xv[0] = p.val[t];
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) row[u] = p.idx[t + u];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u)
-                xv[u] = (unsigned)row[u] < (unsigned)p.n_in ? p.x_full[row[u]] : 0.f;
-        }
-        // an index outside the matrix reads row 0 with multiplier 0
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            if ((unsigned)row[u] >= (unsigned)p.n_in) { row[u] = 0; xv[u] = 0.f; }
-    };
+    auto fetch_full = [&](int t) { fetch_pairs(t, row, xv); settle_pairs(row, xv); };
 
     if (n_full > 0) fetch_full(t0);
     for (int it = 0; it < n_full; ++it) {
@@ -229,7 +225,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
                 const int r = ident ? t : p.idx[t];
                 if ((unsigned)r < (unsigned)p.n_in) {
                     row[u] = r;
-                    xv[u] = p.val ? p.val[t] : p.x_full[r];
+                    xv[u] = p.val[t];
                 }
             }
         }
@@ -627,6 +623,20 @@ hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t str
     if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
     if (p.dtype == DIP_INT4_G128) return launch_lpr<q4_t>(p, s, stream, pk);
     return hipErrorInvalidValue;
+}
+
+__global__ void gather_kernel(const float* x, const int32_t* idx, int k, int n, float* val, int32_t* idx_copy) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= k) return;
+    const int r = idx[t];
+    idx_copy[t] = r;
+    val[t] = (unsigned)r < (unsigned)n ? x[r] : 0.f;
+}
+
+hipError_t launch_gather(const float* x, const int32_t* idx, int k, int n, float* val, int32_t* idx_copy,
+                         hipStream_t stream) {
+    hipLaunchKernelGGL(gather_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, x, idx, k, n, val, idx_copy);
+    return hipGetLastError();
 }
 
 hipError_t launch_rowdot(const RowdotParams& p, hipStream_t stream, int prof_kind) {

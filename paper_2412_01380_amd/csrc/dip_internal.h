@@ -92,9 +92,8 @@ struct GemvParams {
     int n_in;                 // stored rows
     int n_out;                // elements per row actually produced per segment
     int nseg;                 // 1: plain GEMV;  2: bundled [up ; gate] with SwiGLU epilogue
-    const int32_t* idx;       // k ascending row indices; null: rows 0..k-1 (val must be given)
-    const float* val;         // compact: val[t] multiplies row idx[t];  or
-    const float* x_full;      // full vector: x_full[idx[t]] multiplies row idx[t] (val == null)
+    const int32_t* idx;       // k ascending row indices (16-byte aligned); null: rows 0..k-1
+    const float* val;         // val[t] multiplies row idx[t] (16-byte aligned)
     int k;
     int rows_per_split;       // ceil(k / ksplit), filled in by launch_gemv
     float* out;               // n_out floats (nseg == 2: the GLU output, n_out = d_ff)
@@ -126,6 +125,9 @@ hipError_t launch_rowdot(const RowdotParams& p, hipStream_t stream, int prof_kin
 GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k);
 int gemv_strips(const GemvShape& s, int dtype, int n_out);
 hipError_t launch_gemv(const GemvParams& p, const GemvShape& s, hipStream_t stream, int prof_kind);
+// val[t] = x[idx[t]] (0 for an index outside [0, n)) and idx_copy[t] = idx[t], for t < k
+hipError_t launch_gather(const float* x, const int32_t* idx, int k, int n, float* val, int32_t* idx_copy,
+                         hipStream_t stream);
 
 extern GemvShape g_gemv_override;
 
