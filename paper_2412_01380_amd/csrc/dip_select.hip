@@ -11,17 +11,14 @@
 //
 // top-K is a most-significant-digit radix select (12 + 10 + 10 bits) on the 32-bit key
 // patterns; non-negative floats order like their bit patterns.  The first digit is
-// histogrammed from the registers; the keys that fall into the threshold bin (a few per
-// cent of the vector) are then compacted into LDS and the two remaining digits only look
-// at those.  The same routine, on the age (current step - stamp) of the evictable
-// columns, picks eviction victims (smallest (stamp, index) first).
+// histogrammed from the registers; the two remaining digits only look at the keys that fall
+// into the threshold bin (a few per cent of the vector).  Eviction victims (smallest
+// (stamp, index) first) are the largest ages (current step - stamp) among the evictable
+// columns, found by the same radix select.
 #include "dip_internal.h"
 
 #ifndef SEL_WRITELANE
 #define SEL_WRITELANE 0
-#endif
-#ifndef SEL_SEGMENTS
-#define SEL_SEGMENTS 0
 #endif
 
 namespace dip {
@@ -30,8 +27,6 @@ namespace {
 constexpr int kWaves = kSelThreads / 64;            // 16
 constexpr int kMaxItems = DIP_MAX_N / kSelThreads;  // 32
 constexpr int kMaxTiles = kMaxItems * kWaves;       // 512
-constexpr int kCandSeg = 256;                       // threshold-bin keys one wavefront may park in LDS
-constexpr int kCandCap = kCandSeg * kWaves;         // 4096
 constexpr int kBinsA = 4096, kBinsB = 1024, kBinsC = 1024;
 
 constexpr int kVicCap = 12288;   // evictable columns whose (age, index) fit the LDS list
@@ -39,7 +34,6 @@ constexpr int kMaxWords = DIP_MAX_N / 32;  // 1024: one residency / mask word pe
 
 struct SelShared {
     uint32_t hist[kBinsA + kBinsB + kBinsC];
-    uint32_t cand[kCandCap];
     uint32_t vkey[kVicCap];          // eviction keys of the evictable columns, ascending index
     uint16_t vidx[kVicCap];          // ... and their column indices
     uint32_t cw[kMaxWords];          // residency words (the paper's c)
@@ -50,7 +44,6 @@ struct SelShared {
     float wave_max[kWaves];
     uint32_t bcast[4];
     uint32_t cnt[8];
-    uint32_t wcnt[kWaves];  // threshold-bin keys found by each wavefront
 };
 
 // Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel primitives:
@@ -168,52 +161,20 @@ __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS
     find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
     uint32_t remaining = k - above;
 
-    // Keys of the threshold bin -> LDS, each wavefront into its own segment (their order is
-    // irrelevant for finding the threshold).  A wavefront that finds more than a segment
-    // holds -- tie storms -- sends the remaining digits down the register path instead.
-    const int wave = tid >> 6;
-    uint32_t* seg = sh.cand + wave * kCandSeg;
-    uint32_t wcount = 0;
+    // digit 2: bits 19..10, only the keys of the threshold bin (a few per cent of the vector)
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const bool hit = (key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u);
-        const uint64_t bh = __ballot(hit);
-        if (hit) {
-            const uint32_t off = wcount + lanes_below(bh);
-            if (off < (uint32_t)kCandSeg) seg[off] = key[j];
-        }
-        wcount += (uint32_t)__popcll(bh);
-    }
-    if (lane == 0) sh.wcnt[wave] = wcount;
-    __syncthreads();
-    uint32_t wmax = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) wmax = max(wmax, sh.wcnt[w]);
-    const bool compact = SEL_SEGMENTS && wmax <= (uint32_t)kCandSeg;
-
-    // digit 2: bits 19..10
-    if (compact) {
-#pragma unroll
-        for (int q = 0; q < kCandCap / kSelThreads; ++q) {
-            const int slot = q * kSelThreads + tid;       // segment = slot / kCandSeg
-            if ((uint32_t)(slot % kCandSeg) < sh.wcnt[slot / kCandSeg])
-                atomicAdd(&histB[(sh.cand[slot] >> 10) & 1023u], 1u);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if ((key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u)) {
-                // merge the lanes of a wavefront that share the digit of its first caller
-                const uint32_t d = (key[j] >> 10) & 1023u;
-                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-                const uint64_t same = __ballot(d == d0);
-                if (d == d0) {
-                    if (lanes_below(same) == 0u) atomicAdd(&histB[d0], (uint32_t)__popcll(same));
-                } else {
-                    atomicAdd(&histB[d], 1u);
-                }
+    for (int j = 0; j < ITEMS; ++j)
+        if ((key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u)) {
+            // merge the lanes of a wavefront that share the digit of its first caller
+            const uint32_t d = (key[j] >> 10) & 1023u;
+            const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+            const uint64_t same = __ballot(d == d0);
+            if (d == d0) {
+                if (lanes_below(same) == 0u) atomicAdd(&histB[d0], (uint32_t)__popcll(same));
+            } else {
+                atomicAdd(&histB[d], 1u);
             }
-    }
+        }
     __syncthreads();
     uint32_t b2;
     find_bin<1>(histB, remaining, sh, phase, b2, above, inbin);
@@ -221,29 +182,18 @@ __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS
     const uint32_t hi = (b1 << 10) | b2;
 
     // digit 3: bits 9..0
-    if (compact) {
 #pragma unroll
-        for (int q = 0; q < kCandCap / kSelThreads; ++q) {
-            const int slot = q * kSelThreads + tid;
-            if ((uint32_t)(slot % kCandSeg) < sh.wcnt[slot / kCandSeg]) {
-                const uint32_t kk = sh.cand[slot];
-                if ((kk >> 10) == hi) atomicAdd(&histC[kk & 1023u], 1u);
+    for (int j = 0; j < ITEMS; ++j)
+        if ((key[j] >> 10) == hi && (!SKIP_ZERO || key[j] != 0u)) {
+            const uint32_t d = key[j] & 1023u;
+            const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+            const uint64_t same = __ballot(d == d0);
+            if (d == d0) {
+                if (lanes_below(same) == 0u) atomicAdd(&histC[d0], (uint32_t)__popcll(same));
+            } else {
+                atomicAdd(&histC[d], 1u);
             }
         }
-    } else {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if ((key[j] >> 10) == hi && (!SKIP_ZERO || key[j] != 0u)) {
-                const uint32_t d = key[j] & 1023u;
-                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-                const uint64_t same = __ballot(d == d0);
-                if (d == d0) {
-                    if (lanes_below(same) == 0u) atomicAdd(&histC[d0], (uint32_t)__popcll(same));
-                } else {
-                    atomicAdd(&histC[d], 1u);
-                }
-            }
-    }
     __syncthreads();
     uint32_t b3;
     find_bin<1>(histC, remaining, sh, phase, b3, above, inbin);
@@ -541,7 +491,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
             }
         }
 
-        const bool need_stamps = n_evict > 0 || p.policy == DIP_LFU;
+        // When the misses outnumber the room that evictions can make (the active set does not
+        // fit: Sec. 6.3), every evictable column goes and nothing has to be ranked.
+        const bool evict_all = n_evict > 0 && n_evict == n_vic;
+        const bool need_stamps = (n_evict > 0 && !evict_all) || p.policy == DIP_LFU;
         uint32_t stamp_old[ITEMS];
         if (need_stamps) {
 #pragma unroll
@@ -550,7 +503,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
                 stamp_old[j] = ((valid >> j) & 1u) ? p.c_stamp[i] : 0u;
             }
         }
-        if (n_evict > 0) {
+        if (evict_all) {
+            sh.cw[tid] = c & ~vicw;
+            __syncthreads();
+        } else if (n_evict > 0) {
             // Eviction key of an evictable column: its age t_now - stamp (LRU: steps since
             // last use, LFU: how far its use count lags the step counter), moved up so that
             // the top bit of t_now becomes bit 31.  The oldest / least used has the largest
