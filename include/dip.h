@@ -150,6 +150,25 @@ typedef struct dip_partial_debug {
     float* h_sel;   /* k values of GLU~(x) at those units (16-byte aligned)                 */
 } dip_partial_debug;
 
+/* A weight matrix kept in two tiers (Sec. 5: a small fast memory caching columns of a large
+ * slow one).  `full` describes the whole feature-major matrix in PINNED HOST memory that the
+ * GPU can read directly (full.data is that device-accessible host pointer); `slots` is the
+ * fast tier: `capacity` rows of full.row_stride_bytes in HBM.  Column i is resident -- bit i
+ * of the cache's residency mask -- exactly when slot_of[i] >= 0, and then slots row
+ * slot_of[i] holds a copy of stored row i.  F32 and BF16 only. */
+typedef struct dip_tiered_weight {
+    dip_weight full;     /* data: host memory, device-accessible                            */
+    void* slots;         /* device; capacity rows, 16-byte aligned                          */
+    int32_t* slot_of;    /* device; full.n_in entries                                       */
+    int32_t capacity;    /* slots; must equal the capacity of the cache used with it        */
+    int32_t reserved;    /* must be 0                                                       */
+} dip_tiered_weight;
+
+typedef struct dip_tiered_mlp {
+    dip_tiered_weight w_ug; /* bundled up/gate, as in dip_mlp                              */
+    dip_tiered_weight w_d;
+} dip_tiered_mlp;
+
 /* (major << 16) | minor. */
 int32_t dip_version(void);
 
@@ -200,6 +219,20 @@ int32_t dip_cache_init(const dip_cache* cache, const uint32_t* initial_bits, voi
  * Advances meta[DIP_META_STEP] and refreshes the other meta counters.
  */
 int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void* stream);
+
+/*
+ * Checkpoint helpers for a cache (the state survives between tokens, Alg. 1 returns c^(t)).
+ * dip_cache_state_bytes: sizes of the three caller-owned arrays for n columns (host outputs,
+ * each may be NULL).  dip_cache_export / dip_cache_import copy the whole state to / from one
+ * contiguous blob of dip_cache_blob_bytes(n) bytes laid out [bits | stamp | meta], each part
+ * starting on a 256-byte boundary; the blob may be device memory or host memory (pinned
+ * host memory keeps the copy asynchronous).  Copies are enqueued on the stream.
+ */
+int32_t dip_cache_state_bytes(int32_t n, size_t* bits_bytes /* host */, size_t* stamp_bytes /* host */,
+                              size_t* meta_bytes /* host */);
+size_t dip_cache_blob_bytes(int32_t n);
+int32_t dip_cache_export(const dip_cache* cache, void* blob, size_t blob_bytes, void* stream);
+int32_t dip_cache_import(const dip_cache* cache, const void* blob, size_t blob_bytes, void* stream);
 
 /*
  * Column-gathered matrix-vector product, Alg. 1 step 4 (W~ = W (.) m) applied to x:
@@ -301,6 +334,26 @@ int32_t dip_partial_pruning_forward(const dip_mlp_split* mlp, int32_t scheme, co
                                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Two-tier residency made real (Sec. 5, Fig. 4; Alg. 1's c decides what the fast tier holds).
+ * dip_tier_init: after dip_cache_init, give every resident column a slot (the r-th resident
+ * column, ascending, gets slot r), copy those rows host -> HBM, mark the others slot_of = -1.
+ * dip_tiered_mlp_forward: dip_swiglu_mlp_forward with both caches mandatory, where after each
+ * cache update the inserted columns take over the slots of the evicted ones (i-th inserted,
+ * ascending, <- slot of the i-th evicted; the rest get slots never used before), their rows
+ * are copied host -> HBM, and the gathered product reads resident columns from their slots
+ * and the misses that found no room (Sec. 6.3) straight from host memory.  y is bit-identical
+ * to dip_swiglu_mlp_forward on the same inputs and cache states.
+ */
+size_t dip_tier_init_workspace_bytes(const dip_tiered_weight* tw);
+int32_t dip_tier_init(const dip_tiered_weight* tw, const dip_cache* cache, void* ws, size_t ws_bytes,
+                      void* stream);
+size_t dip_tiered_mlp_forward_workspace_bytes(const dip_tiered_mlp* mlp, int32_t k_in, int32_t k_mid);
+int32_t dip_tiered_mlp_forward(const dip_tiered_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                               const dip_cache* cache_in, const dip_cache* cache_mid, float gamma,
+                               float* y_out, const dip_debug* dbg, void* ws, size_t ws_bytes,
+                               void* stream);
+
+/*
  * Launch-shape override for the gathered GEMV kernels, for tuning sweeps.  0 restores the
  * built-in choice for that parameter.  Host-side, process-wide, not thread-safe against
  * concurrent launches.
@@ -334,7 +387,8 @@ int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, i
 #define DIP_KERNEL_GEMV_DOWN 3   /* gathered down GEMV (also dip_gathered_gemv)             */
 #define DIP_KERNEL_GEMV_DENSE 4  /* dense first product of gate / up pruning                */
 #define DIP_KERNEL_ROWDOT 5      /* row-gathered dot products                               */
-#define DIP_KERNEL_KINDS 6
+#define DIP_KERNEL_TIER_FILL 6   /* host -> HBM copies of the columns a cache update inserted  */
+#define DIP_KERNEL_KINDS 7
 int32_t dip_profile_enable(int32_t max_launches);
 int32_t dip_profile_read(int32_t kind, double* total_ms /* host */, int32_t* launches /* host */);
 int32_t dip_profile_disable(void);

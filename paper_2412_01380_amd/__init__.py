@@ -13,6 +13,9 @@ from .libdip import (  # noqa: F401
     dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack,
     dip_swiglu_mlp_forward_workspace_bytes, dip_tune_gemv, dip_version, MlpStack, EXPORTS, META,
     dip_gemv_launch_shape, dip_profile_enable,
+    dip_cache_state_bytes, dip_cache_blob_bytes, dip_cache_export, dip_cache_import,
+    TieredWeight, TieredMlp, dip_tier_init, dip_tier_init_workspace_bytes, dip_tiered_mlp_forward,
+    dip_tiered_mlp_forward_workspace_bytes,
     DIP_GATE_PRUNING, DIP_UP_PRUNING, MlpSplit, PartialDebug, glu_debug, dip_glu_pruning_forward,
     dip_glu_pruning_forward_workspace_bytes, dip_gathered_rowdot, dip_partial_pruning_forward,
     dip_partial_pruning_forward_workspace_bytes,

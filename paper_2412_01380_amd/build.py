@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIBPATH = os.path.join(LIBDIR, "libdip.so")
-SOURCES = ["dip_api.hip", "dip_select.hip", "dip_gemv.hip", "dip_batched.hip"]
+SOURCES = ["dip_api.hip", "dip_select.hip", "dip_gemv.hip", "dip_batched.hip", "dip_tier.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -272,6 +272,51 @@ int32_t dip_cache_update(const dip_cache* cache, const uint32_t* mask_bits, void
     return check_hip(launch_select(p, static_cast<hipStream_t>(stream), DIP_KERNEL_SELECT_IN), "dip_cache_update");
 }
 
+int32_t dip_cache_state_bytes(int32_t n, size_t* bits_bytes, size_t* stamp_bytes, size_t* meta_bytes) {
+    if (n < 1 || n > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "dip_cache_state_bytes: n must be in [1, %d]", DIP_MAX_N);
+    if (bits_bytes) *bits_bytes = sizeof(uint32_t) * (size_t)((n + 31) / 32);
+    if (stamp_bytes) *stamp_bytes = sizeof(uint32_t) * (size_t)n;
+    if (meta_bytes) *meta_bytes = sizeof(uint32_t) * DIP_CACHE_META_WORDS;
+    return DIP_OK;
+}
+
+size_t dip_cache_blob_bytes(int32_t n) {
+    if (n < 1 || n > DIP_MAX_N) return 0;
+    return align_up(sizeof(uint32_t) * (size_t)((n + 31) / 32), 256) + align_up(sizeof(uint32_t) * (size_t)n, 256) +
+           align_up(sizeof(uint32_t) * DIP_CACHE_META_WORDS, 256);
+}
+
+static int32_t cache_blob_copy(const dip_cache* cache, void* blob, size_t blob_bytes, void* stream,
+                               bool to_blob, const char* name) {
+    if (!cache || !blob) return fail(DIP_ERR_INVALID_ARG, "%s: null pointer", name);
+    int32_t st = validate_cache(cache, -1, name);
+    if (st) return st;
+    if (blob_bytes < dip_cache_blob_bytes(cache->n))
+        return fail(DIP_ERR_INVALID_ARG, "%s: blob smaller than dip_cache_blob_bytes(n)", name);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* b = static_cast<char*>(blob);
+    const size_t nb = sizeof(uint32_t) * (size_t)((cache->n + 31) / 32), ns = sizeof(uint32_t) * (size_t)cache->n;
+    const size_t nm = sizeof(uint32_t) * DIP_CACHE_META_WORDS;
+    void* part[3] = {cache->bits, cache->stamp, cache->meta};
+    const size_t bytes[3] = {nb, ns, nm};
+    size_t off = 0;
+    for (int i = 0; i < 3; ++i) {
+        hipError_t e = to_blob ? hipMemcpyAsync(b + off, part[i], bytes[i], hipMemcpyDefault, hs)
+                               : hipMemcpyAsync(part[i], b + off, bytes[i], hipMemcpyDefault, hs);
+        if ((st = check_hip(e, name))) return st;
+        off += align_up(bytes[i], 256);
+    }
+    return DIP_OK;
+}
+
+int32_t dip_cache_export(const dip_cache* cache, void* blob, size_t blob_bytes, void* stream) {
+    return cache_blob_copy(cache, blob, blob_bytes, stream, true, "dip_cache_export");
+}
+
+int32_t dip_cache_import(const dip_cache* cache, const void* blob, size_t blob_bytes, void* stream) {
+    return cache_blob_copy(cache, const_cast<void*>(blob), blob_bytes, stream, false, "dip_cache_import");
+}
+
 size_t dip_gathered_gemv_workspace_bytes(const dip_weight* w, int32_t k) {
     if (!w || w->n_out < 1 || k < 1) return 0;
     if (w->dtype != DIP_F32 && w->dtype != DIP_BF16 && w->dtype != DIP_INT4_G128) return 0;
@@ -661,6 +706,176 @@ int32_t dip_partial_pruning_forward(const dip_mlp_split* mlp, int32_t scheme, co
     g2.idx = idx; g2.val = hsel; g2.k = k; g2.out = y_out;
     g2.partial = reinterpret_cast<float*>(base + pl.off_part_dn); g2.counters = cnt_dn;
     return check_hip(launch_gemv(g2, pl.dn, hs, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+}
+
+// ---- two-tier residency ------------------------------------------------------------------------
+namespace {
+int32_t validate_tier(const dip_tiered_weight* tw, const dip_cache* cache, const char* name) {
+    if (!tw) return fail(DIP_ERR_INVALID_ARG, "%s: null descriptor", name);
+    int32_t st = validate_weight(&tw->full, name);
+    if (st) return st;
+    if (tw->full.dtype == DIP_INT4_G128) return fail(DIP_ERR_UNSUPPORTED, "%s: tiers hold F32 or BF16 matrices", name);
+    if (tw->full.n_in > DIP_MAX_N) return fail(DIP_ERR_UNSUPPORTED, "%s: more than %d columns", name, DIP_MAX_N);
+    if (!tw->slots || !tw->slot_of) return fail(DIP_ERR_INVALID_ARG, "%s: null slots or slot_of", name);
+    if (!aligned(tw->slots, 16)) return fail(DIP_ERR_UNSUPPORTED, "%s: slots must be 16-byte aligned", name);
+    if (tw->reserved != 0) return fail(DIP_ERR_INVALID_ARG, "%s: reserved must be 0", name);
+    if (tw->capacity < 0 || tw->capacity > tw->full.n_in) return fail(DIP_ERR_INVALID_ARG, "%s: capacity outside [0, n_in]", name);
+    if (!cache) return fail(DIP_ERR_INVALID_ARG, "%s: a tiered matrix needs its cache", name);
+    if ((st = validate_cache(cache, tw->full.n_in, name))) return st;
+    if (cache->capacity != tw->capacity) return fail(DIP_ERR_INVALID_ARG, "%s: cache and tier capacities differ", name);
+    return DIP_OK;
+}
+
+struct TierScratch {   // per pruning point, inside the workspace
+    size_t off_ev, off_ins, off_fcol, off_fslot, off_fcnt, off_src, bytes;
+};
+TierScratch plan_tier(int n, int capacity, int k) {
+    TierScratch t;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    t.off_ev = take(sizeof(uint32_t) * ((n + 31) / 32));
+    t.off_ins = take(sizeof(uint32_t) * ((n + 31) / 32));
+    t.off_fcol = take(sizeof(int32_t) * (size_t)std::max(capacity, 1));
+    t.off_fslot = take(sizeof(int32_t) * (size_t)std::max(capacity, 1));
+    t.off_fcnt = take(sizeof(uint32_t));
+    t.off_src = take(sizeof(int32_t) * (size_t)std::max(k, 1));
+    t.bytes = o;
+    return t;
+}
+dip_mlp as_mlp(const dip_tiered_mlp* m) {
+    dip_mlp r;
+    r.w_ug = m->w_ug.full;
+    r.w_d = m->w_d.full;
+    return r;
+}
+}  // namespace
+
+size_t dip_tier_init_workspace_bytes(const dip_tiered_weight* tw) {
+    if (!tw || tw->capacity < 0) return 0;
+    return plan_tier(tw->full.n_in, tw->capacity, 1).bytes;
+}
+
+int32_t dip_tier_init(const dip_tiered_weight* tw, const dip_cache* cache, void* ws, size_t ws_bytes,
+                      void* stream) {
+    int32_t st = validate_tier(tw, cache, "dip_tier_init");
+    if (st) return st;
+    const TierScratch ts = plan_tier(tw->full.n_in, tw->capacity, 1);
+    if (!ws || ws_bytes < ts.bytes || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "dip_tier_init: workspace must be 256-aligned and >= %zu bytes", ts.bytes);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    TierInitParams ip;
+    ip.bits = cache->bits; ip.n = tw->full.n_in; ip.slot_of = tw->slot_of;
+    ip.fill_col = reinterpret_cast<int32_t*>(base + ts.off_fcol);
+    ip.fill_slot = reinterpret_cast<int32_t*>(base + ts.off_fslot);
+    ip.fill_count = reinterpret_cast<uint32_t*>(base + ts.off_fcnt);
+    if ((st = check_hip(launch_tier_init(ip, hs), "dip_tier_init: slot map"))) return st;
+    TierFillParams fp;
+    fp.host_rows = tw->full.data; fp.slots = tw->slots; fp.row_stride = tw->full.row_stride_bytes;
+    fp.row_bytes = (int64_t)tw->full.n_out * elem_bits(tw->full.dtype) / 8;
+    fp.fill_col = ip.fill_col; fp.fill_slot = ip.fill_slot; fp.fill_count = ip.fill_count;
+    fp.max_rows = tw->capacity;
+    return check_hip(launch_tier_fill(fp, hs, -1), "dip_tier_init: fill");
+}
+
+size_t dip_tiered_mlp_forward_workspace_bytes(const dip_tiered_mlp* mlp, int32_t k_in, int32_t k_mid) {
+    if (!mlp) return 0;
+    const dip_mlp m = as_mlp(mlp);
+    if (validate_mlp(&m, k_in, k_mid)) return 0;
+    return align_up(plan_forward(&m, k_in, k_mid).total, 256) +
+           plan_tier(m.w_ug.n_in, mlp->w_ug.capacity, k_in).bytes +
+           plan_tier(m.w_d.n_in, mlp->w_d.capacity, k_mid).bytes;
+}
+
+int32_t dip_tiered_mlp_forward(const dip_tiered_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                               const dip_cache* cache_in, const dip_cache* cache_mid, float gamma,
+                               float* y_out, const dip_debug* dbg, void* ws, size_t ws_bytes,
+                               void* stream) {
+    if (!mlp) return fail(DIP_ERR_INVALID_ARG, "dip_tiered_mlp_forward: null mlp descriptor");
+    if (!x || !y_out) return fail(DIP_ERR_INVALID_ARG, "dip_tiered_mlp_forward: null x or y_out");
+    const dip_mlp m = as_mlp(mlp);
+    int32_t st = validate_mlp(&m, k_in, k_mid);
+    if (st) return st;
+    if ((st = validate_tier(&mlp->w_ug, cache_in, "w_ug"))) return st;
+    if ((st = validate_tier(&mlp->w_d, cache_mid, "w_d"))) return st;
+    if ((st = validate_gamma(gamma))) return st;
+    if (dbg && (!aligned(dbg->idx_in, 16) || !aligned(dbg->idx_mid, 16)))
+        return fail(DIP_ERR_UNSUPPORTED, "dip_tiered_mlp_forward: debug index lists must be 16-byte aligned");
+    const size_t need = dip_tiered_mlp_forward_workspace_bytes(mlp, k_in, k_mid);
+    if (!ws || ws_bytes < need || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "dip_tiered_mlp_forward: workspace must be 256-aligned and >= %zu bytes", need);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const ForwardPlan pl = plan_forward(&m, k_in, k_mid);
+    char* base = static_cast<char*>(ws);
+    char* tbase[2];
+    tbase[0] = base + align_up(pl.total, 256);
+    const TierScratch ts[2] = {plan_tier(pl.d, mlp->w_ug.capacity, k_in), plan_tier(pl.f, mlp->w_d.capacity, k_mid)};
+    tbase[1] = tbase[0] + ts[0].bytes;
+
+    int32_t* idx[2] = {reinterpret_cast<int32_t*>(base + pl.off_idx1), reinterpret_cast<int32_t*>(base + pl.off_idx2)};
+    float* val[2] = {reinterpret_cast<float*>(base + pl.off_val1), reinterpret_cast<float*>(base + pl.off_val2)};
+    float* h = reinterpret_cast<float*>(base + pl.off_h);
+    if (dbg && dbg->idx_in) idx[0] = dbg->idx_in;
+    if (dbg && dbg->idx_mid) idx[1] = dbg->idx_mid;
+    if (dbg && dbg->h) h = dbg->h;
+    uint32_t* cnt_ug = reinterpret_cast<uint32_t*>(base + pl.off_cnt);
+    uint32_t* cnt_dn = cnt_ug + pl.strips_ug;
+
+    for (int pt = 0; pt < 2; ++pt) {
+        const dip_tiered_weight& tw = pt == 0 ? mlp->w_ug : mlp->w_d;
+        const dip_cache* cache = pt == 0 ? cache_in : cache_mid;
+        const int n = pt == 0 ? pl.d : pl.f, k = pt == 0 ? k_in : k_mid;
+        char* tb = tbase[pt];
+        uint32_t* evw = reinterpret_cast<uint32_t*>(tb + ts[pt].off_ev);
+        uint32_t* insw = reinterpret_cast<uint32_t*>(tb + ts[pt].off_ins);
+        int32_t* fcol = reinterpret_cast<int32_t*>(tb + ts[pt].off_fcol);
+        int32_t* fslot = reinterpret_cast<int32_t*>(tb + ts[pt].off_fslot);
+        uint32_t* fcnt = reinterpret_cast<uint32_t*>(tb + ts[pt].off_fcnt);
+        int32_t* src = reinterpret_cast<int32_t*>(tb + ts[pt].off_src);
+
+        // Alg. 1 steps 1-3, plus the words of what the update evicted and inserted
+        SelectParams sp;
+        std::memset(&sp, 0, sizeof(sp));
+        sp.v = pt == 0 ? x : h; sp.n = n; sp.k = k; sp.gamma = gamma;
+        sp.s_out = dbg ? (pt == 0 ? dbg->s_in : dbg->s_mid) : nullptr;
+        sp.mask_out = dbg ? (pt == 0 ? dbg->mask_in : dbg->mask_mid) : nullptr;
+        sp.idx_out = idx[pt]; sp.val_out = val[pt];
+        sp.score_bits = cache->bits; sp.c_bits = cache->bits; sp.c_stamp = cache->stamp; sp.c_meta = cache->meta;
+        sp.capacity = cache->capacity; sp.policy = cache->policy;
+        sp.evicted_out = evw; sp.inserted_out = insw;
+        if (pt == 0) { sp.zero_ptr = cnt_ug; sp.zero_n = pl.strips_ug + pl.strips_dn; }
+        if ((st = check_hip(launch_select(sp, hs, pt == 0 ? DIP_KERNEL_SELECT_IN : DIP_KERNEL_SELECT_MID), "select"))) return st;
+
+        // slots for the inserted columns, rows to copy, rows to read
+        TierParams tp;
+        tp.evicted = evw; tp.inserted = insw; tp.meta = cache->meta; tp.n = n; tp.capacity = tw.capacity;
+        tp.slot_of = tw.slot_of; tp.fill_col = fcol; tp.fill_slot = fslot; tp.fill_count = fcnt;
+        tp.idx = idx[pt]; tp.k = k; tp.src = src;
+        if ((st = check_hip(launch_tier_update(tp, hs), "tier update"))) return st;
+        TierFillParams fp;
+        fp.host_rows = tw.full.data; fp.slots = tw.slots; fp.row_stride = tw.full.row_stride_bytes;
+        fp.row_bytes = (int64_t)tw.full.n_out * elem_bits(tw.full.dtype) / 8;
+        fp.fill_col = fcol; fp.fill_slot = fslot; fp.fill_count = fcnt;
+        fp.max_rows = std::min(k, tw.capacity);
+        if ((st = check_hip(launch_tier_fill(fp, hs, DIP_KERNEL_TIER_FILL), "tier fill"))) return st;
+
+        GemvParams g;
+        std::memset(&g, 0, sizeof(g));
+        g.w = tw.slots; g.n_in = tw.capacity; g.w_alt = tw.full.data; g.n_alt = n;
+        g.row_stride = tw.full.row_stride_bytes; g.dtype = tw.full.dtype;
+        g.idx = src; g.val = val[pt]; g.k = k;
+        if (pt == 0) {
+            g.n_out = pl.f; g.nseg = 2; g.out = h;
+            g.partial = reinterpret_cast<float*>(base + pl.off_part_ug); g.counters = cnt_ug;
+            st = check_hip(launch_gemv(g, pl.ug, hs, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
+        } else {
+            g.n_out = pl.d; g.nseg = 1; g.out = y_out;
+            g.partial = reinterpret_cast<float*>(base + pl.off_part_dn); g.counters = cnt_dn;
+            st = check_hip(launch_gemv(g, pl.dn, hs, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+        }
+        if (st) return st;
+    }
+    return DIP_OK;
 }
 
 int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out) {

@@ -128,6 +128,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     }
 
     const char* wbase = static_cast<const char*>(p.w) + (size_t)col * Elem<WT>::kBits / 8;
+    const char* abase = p.w_alt ? static_cast<const char*>(p.w_alt) + (size_t)col * Elem<WT>::kBits / 8 : wbase;
     const size_t seg_bytes = (size_t)p.n_out * Elem<WT>::kBits / 8;
     // quantised rows: the scale of this lane's 32 codes (all inside one group of 128)
     const int sgroup = col >> 7, sgroups_per_seg = p.n_out >> 7;
@@ -165,18 +166,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             if (!ident) row[0] = p.idx[t];
         }
     };
-    // an index outside the matrix reads row 0 with multiplier 0
-    auto settle_pairs = [&](int (&row)[UNROLL], float (&xv)[UNROLL]) {
+    // A list entry r >= 0 is stored row r of p.w; an entry r < 0 is stored row ~r of the second
+    // matrix p.w_alt (two-tier residency: the copy of the full matrix in host memory).  An
+    // entry outside its matrix reads row 0 with multiplier 0.
+    auto settle_pairs = [&](int (&row)[UNROLL], float (&xv)[UNROLL], uint32_t& alt) {
+        alt = 0u;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const bool inside = (unsigned)row[u] < (unsigned)p.n_in;
-            row[u] = inside ? row[u] : 0;
+            const bool second = row[u] < 0;
+            const int r = second ? ~row[u] : row[u];
+            const bool inside = (unsigned)r < (unsigned)(second ? p.n_alt : p.n_in);
+            row[u] = inside ? r : 0;
             xv[u] = inside ? xv[u] : 0.f;
+            alt |= (inside && second) ? (1u << u) : 0u;
         }
     };
     int row[UNROLL];
     float xv[UNROLL];
-    auto fetch_full = [&](int t) { fetch_pairs(t, row, xv); settle_pairs(row, xv); };
+    uint32_t alt = 0u;
+    auto fetch_full = [&](int t) { fetch_pairs(t, row, xv); settle_pairs(row, xv, alt); };
 
     if (n_full > 0) fetch_full(t0);
     for (int it = 0; it < n_full; ++it) {
@@ -186,10 +194,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const size_t off = (size_t)row[u] * (size_t)p.row_stride;
+            const char* src = ((alt >> u) & 1u) ? abase : wbase;
             xc[u] = xv[u];
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
-                q[u][s] = load16(wbase + off + s * seg_bytes);
+                q[u][s] = load16(src + off + s * seg_bytes);
                 if constexpr (Elem<WT>::kScaled)
                     sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
             }
@@ -222,10 +231,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             row[u] = -1;
             xv[u] = 0.f;
             if (t < ke) {
-                const int r = ident ? t : p.idx[t];
-                if ((unsigned)r < (unsigned)p.n_in) {
+                const int e = ident ? t : p.idx[t];
+                const bool second = e < 0;
+                const int r = second ? ~e : e;
+                if ((unsigned)r < (unsigned)(second ? p.n_alt : p.n_in)) {
                     row[u] = r;
                     xv[u] = p.val[t];
+                    alt = second ? (alt | (1u << u)) : (alt & ~(1u << u));
                 }
             }
         }
@@ -236,7 +248,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
                 q[u][s] = u32x4{0u, 0u, 0u, 0u};
                 sc[u][s] = 0;
                 if (row[u] >= 0) {
-                    q[u][s] = load16(wbase + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
+                    const char* src = ((alt >> u) & 1u) ? abase : wbase;
+                    q[u][s] = load16(src + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
                     if constexpr (Elem<WT>::kScaled)
                         sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
                 }

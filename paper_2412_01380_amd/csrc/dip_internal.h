@@ -56,6 +56,9 @@ struct SelectParams {
     // counters the following GEMV launch expects to be zero
     uint32_t* zero_ptr;
     int zero_n;
+    // words of the columns this update evicted / inserted (nullable; only with a cache update)
+    uint32_t* evicted_out;
+    uint32_t* inserted_out;
     // rows > 1: one workgroup per row; row b reads v + b*v_row_stride and writes its mask at
     // mask_out + b*words_row_stride (every other output and the cache update must be off)
     int rows;
@@ -100,6 +103,8 @@ struct GemvParams {
     float* partial;           // [ksplit][nseg][n_out] when ksplit > 1
     uint32_t* counters;       // [strips], zero on entry, when ksplit > 1
     int act;                  // nseg == 1 only: 0 writes the sums, 1 writes SiLU of the sums
+    const void* w_alt;        // second matrix for list entries r < 0 (stored row ~r), same dtype and
+    int n_alt;                // row stride, n_alt rows; null / 0 when there is none
 };
 
 // ---- row-gathered dot products (Sec. 3.2, Gate / Up pruning) ---------------------------------
@@ -173,6 +178,43 @@ int batched_shares(int dtype, int n_out, int k_max);
 hipError_t launch_union(const UnionParams& p, hipStream_t stream);
 hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int prof_kind);
 hipError_t launch_batched_reduce(const BatchedReduceParams& p, hipStream_t stream);
+
+// ---- two-tier residency: slot map of the HBM cache, fill list, encoded row list -----------------
+struct TierParams {
+    const uint32_t* evicted;   // words from the cache update of this token
+    const uint32_t* inserted;
+    const uint32_t* meta;      // the cache's counters after that update
+    int n;                     // columns
+    int capacity;              // slots
+    int32_t* slot_of;          // [n]: slot of a resident column, -1 otherwise
+    int32_t* fill_col;         // [<= capacity] inserted columns ...
+    int32_t* fill_slot;        // ... and the slots they were given
+    uint32_t* fill_count;
+    const int32_t* idx;        // this token's selected columns (k ascending), or null
+    int k;
+    int32_t* src;              // [k]: slot s >= 0 of a resident column, ~column otherwise
+};
+struct TierFillParams {
+    const void* host_rows;     // full matrix, device-accessible host memory
+    void* slots;               // HBM cache
+    int64_t row_stride;        // bytes, both tiers
+    int64_t row_bytes;
+    const int32_t* fill_col;
+    const int32_t* fill_slot;
+    const uint32_t* fill_count;
+    int max_rows;
+};
+struct TierInitParams {
+    const uint32_t* bits;      // residency words
+    int n;
+    int32_t* slot_of;
+    int32_t* fill_col;
+    int32_t* fill_slot;
+    uint32_t* fill_count;
+};
+hipError_t launch_tier_update(const TierParams& p, hipStream_t stream);
+hipError_t launch_tier_fill(const TierFillParams& p, hipStream_t stream, int prof_kind);
+hipError_t launch_tier_init(const TierInitParams& p, hipStream_t stream);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

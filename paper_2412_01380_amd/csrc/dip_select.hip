@@ -566,7 +566,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
             }
             __syncthreads();
         }
-        const uint32_t newc = (sh.cw[tid] & wmask) | insw;
+        const uint32_t kept = sh.cw[tid] & wmask;
+        const uint32_t newc = kept | insw;
+        if (tid < nwords) {
+            if (p.evicted_out) p.evicted_out[tid] = c & ~kept;
+            if (p.inserted_out) p.inserted_out[tid] = insw;
+        }
         __syncthreads();          // every lane has read its word before any is replaced
         sh.cw[tid] = newc;
         if (tid < nwords) p.c_bits[tid] = newc;

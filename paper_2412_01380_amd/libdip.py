@@ -60,6 +60,15 @@ class _PartialDebug(C.Structure):
     _fields_ = [("a", C.c_void_p), ("mask", C.c_void_p), ("idx", C.c_void_p), ("h_sel", C.c_void_p)]
 
 
+class _TieredWeight(C.Structure):
+    _fields_ = [("full", _Weight), ("slots", C.c_void_p), ("slot_of", C.c_void_p),
+                ("capacity", C.c_int32), ("reserved", C.c_int32)]
+
+
+class _TieredMlp(C.Structure):
+    _fields_ = [("w_ug", _TieredWeight), ("w_d", _TieredWeight)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(lib_path):
         raise ImportError(
@@ -79,6 +88,14 @@ def _load() -> C.CDLL:
     L.dip_cache_init.argtypes = [C.POINTER(_Cache), vp, vp]
     L.dip_cache_update.restype = i32
     L.dip_cache_update.argtypes = [C.POINTER(_Cache), vp, vp]
+    L.dip_cache_state_bytes.restype = i32
+    L.dip_cache_state_bytes.argtypes = [i32, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+    L.dip_cache_blob_bytes.restype = sz
+    L.dip_cache_blob_bytes.argtypes = [i32]
+    L.dip_cache_export.restype = i32
+    L.dip_cache_export.argtypes = [C.POINTER(_Cache), vp, sz, vp]
+    L.dip_cache_import.restype = i32
+    L.dip_cache_import.argtypes = [C.POINTER(_Cache), vp, sz, vp]
     L.dip_gathered_gemv_workspace_bytes.restype = sz
     L.dip_gathered_gemv_workspace_bytes.argtypes = [C.POINTER(_Weight), i32]
     L.dip_gathered_gemv.restype = i32
@@ -108,6 +125,15 @@ def _load() -> C.CDLL:
     L.dip_partial_pruning_forward.restype = i32
     L.dip_partial_pruning_forward.argtypes = [C.POINTER(_MlpSplit), i32, vp, i32, vp,
                                               C.POINTER(_PartialDebug), vp, sz, vp]
+    L.dip_tier_init_workspace_bytes.restype = sz
+    L.dip_tier_init_workspace_bytes.argtypes = [C.POINTER(_TieredWeight)]
+    L.dip_tier_init.restype = i32
+    L.dip_tier_init.argtypes = [C.POINTER(_TieredWeight), C.POINTER(_Cache), vp, sz, vp]
+    L.dip_tiered_mlp_forward_workspace_bytes.restype = sz
+    L.dip_tiered_mlp_forward_workspace_bytes.argtypes = [C.POINTER(_TieredMlp), i32, i32]
+    L.dip_tiered_mlp_forward.restype = i32
+    L.dip_tiered_mlp_forward.argtypes = [C.POINTER(_TieredMlp), vp, i32, i32, C.POINTER(_Cache),
+                                         C.POINTER(_Cache), f32, vp, C.POINTER(_Debug), vp, sz, vp]
     L.dip_tune_gemv.restype = i32
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
     L.dip_gemv_launch_shape.restype = i32
@@ -124,12 +150,14 @@ def _load() -> C.CDLL:
 lib = _load()
 
 EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "dip_cache_init",
-           "dip_cache_update", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
+           "dip_cache_update", "dip_cache_state_bytes", "dip_cache_blob_bytes", "dip_cache_export",
+           "dip_cache_import", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
            "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
            "dip_swiglu_mlp_forward_batched", "dip_glu_pruning_forward_workspace_bytes",
            "dip_glu_pruning_forward", "dip_gathered_rowdot",
-           "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
+           "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tier_init_workspace_bytes",
+           "dip_tier_init", "dip_tiered_mlp_forward_workspace_bytes", "dip_tiered_mlp_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
            "dip_profile_disable"]
 
 
@@ -267,6 +295,38 @@ class PartialDebug:
                                self.h_sel.data_ptr())
 
 
+class TieredWeight:
+    """A matrix in two tiers: `host` is the whole feature-major matrix in pinned host memory
+    (fp32, or bf16 given as bfloat16 / int16 / uint16 bit patterns), `capacity` rows of HBM
+    are its cache.  The slot map lives on the device."""
+
+    def __init__(self, host, capacity: int, device="cuda"):
+        import torch
+        if host.is_cuda or not host.is_pinned() or host.dim() != 2 or host.stride(1) != 1:
+            raise TypeError("the slow tier must be a 2-D pinned host tensor with unit inner stride")
+        if host.dtype == torch.float32:
+            dt = DIP_F32
+        elif host.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+            dt = DIP_BF16
+        else:
+            raise TypeError(f"unsupported tier dtype {host.dtype}")
+        self.host, self.capacity = host, capacity
+        self.slots = torch.zeros((max(capacity, 1), host.shape[1]), dtype=host.dtype, device=device)
+        self.slot_of = torch.full((host.shape[0],), -1, dtype=torch.int32, device=device)
+        stride = host.stride(0) * host.element_size()
+        # pinned host memory is mapped into the device's address space at the same address
+        full = _Weight(host.data_ptr(), None, dt, host.shape[0], host.shape[1], 0, stride)
+        self.c = _TieredWeight(full, self.slots.data_ptr(), self.slot_of.data_ptr(), capacity, 0)
+
+
+class TieredMlp:
+    def __init__(self, w_ug: TieredWeight, w_d: TieredWeight):
+        self.w_ug, self.w_d = w_ug, w_d
+        self.c = _TieredMlp(w_ug.c, w_d.c)
+        self.d_model = w_ug.c.full.n_in
+        self.d_ff = w_d.c.full.n_in
+
+
 def dip_version() -> int:
     return lib.dip_version()
 
@@ -291,6 +351,34 @@ def dip_cache_init(cache: Cache, initial_bits=None, stream=None) -> None:
 def dip_cache_update(cache: Cache, mask_bits, stream=None) -> None:
     import torch
     _check(lib.dip_cache_update(C.byref(cache.c), _ptr(mask_bits, torch.int32), _stream(stream)))
+
+
+def dip_cache_state_bytes(n: int):
+    """(bits, stamp, meta) array sizes in bytes for a cache over n columns."""
+    b, s_, m = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(lib.dip_cache_state_bytes(n, C.byref(b), C.byref(s_), C.byref(m)))
+    return b.value, s_.value, m.value
+
+
+def dip_cache_blob_bytes(n: int) -> int:
+    return lib.dip_cache_blob_bytes(n)
+
+
+def _blob_ptr(blob):
+    """Device tensor or (pinned) host tensor -> raw pointer; the C side copies with hipMemcpyDefault."""
+    if not blob.is_contiguous():
+        raise TypeError("blob must be contiguous")
+    return blob.data_ptr()
+
+
+def dip_cache_export(cache: Cache, blob, stream=None) -> None:
+    _check(lib.dip_cache_export(C.byref(cache.c), _blob_ptr(blob), blob.numel() * blob.element_size(),
+                                _stream(stream)))
+
+
+def dip_cache_import(cache: Cache, blob, stream=None) -> None:
+    _check(lib.dip_cache_import(C.byref(cache.c), _blob_ptr(blob), blob.numel() * blob.element_size(),
+                                _stream(stream)))
 
 
 def dip_gathered_gemv_workspace_bytes(w: Weight, k: int) -> int:
@@ -395,6 +483,28 @@ def dip_partial_pruning_forward(mlp: MlpSplit, scheme: int, x, k: int, y_out,
         C.byref(mlp.c), scheme, _ptr(x, torch.float32), k, _ptr(y_out, torch.float32),
         C.byref(dbg.c) if dbg is not None else None, _ptr(ws), ws.numel() * ws.element_size(),
         _stream(stream)))
+
+
+def dip_tier_init_workspace_bytes(tw: TieredWeight) -> int:
+    return lib.dip_tier_init_workspace_bytes(C.byref(tw.c))
+
+
+def dip_tier_init(tw: TieredWeight, cache: Cache, ws, stream=None) -> None:
+    _check(lib.dip_tier_init(C.byref(tw.c), C.byref(cache.c), _ptr(ws), ws.numel() * ws.element_size(),
+                             _stream(stream)))
+
+
+def dip_tiered_mlp_forward_workspace_bytes(mlp: TieredMlp, k_in: int, k_mid: int) -> int:
+    return lib.dip_tiered_mlp_forward_workspace_bytes(C.byref(mlp.c), k_in, k_mid)
+
+
+def dip_tiered_mlp_forward(mlp: TieredMlp, x, k_in: int, k_mid: int, cache_in: Cache, cache_mid: Cache,
+                           gamma: float, y_out, dbg: Optional[Debug], ws, stream=None) -> None:
+    import torch
+    _check(lib.dip_tiered_mlp_forward(
+        C.byref(mlp.c), _ptr(x, torch.float32), k_in, k_mid, C.byref(cache_in.c), C.byref(cache_mid.c),
+        gamma, _ptr(y_out, torch.float32), C.byref(dbg.c) if dbg is not None else None,
+        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def dip_tune_gemv(lanes_per_row: int = 0, waves: int = 0, ksplit: int = 0, unroll: int = 0) -> None:

@@ -125,6 +125,16 @@ def test_cache_argument_validation(D):
     assert L.dip_cache_init(C.byref(c3), None, None) == D.DIP_ERR_UNSUPPORTED
 
 
+def test_cache_blob_sizes_and_validation(D):
+    assert D.dip_cache_blob_bytes(0) == 0 and D.dip_cache_blob_bytes(D.DIP_MAX_N + 1) == 0
+    assert D.dip_cache_blob_bytes(1000) == 256 + 4096 + 256      # 128 B of bits, 4000 B of stamps, 32 B of meta
+    assert D.dip_cache_state_bytes(1000) == (128, 4000, 32)
+    with pytest.raises(D.DipError):
+        D.dip_cache_state_bytes(0)
+    assert D.lib.dip_cache_export(None, None, 0, None) == D.DIP_ERR_INVALID_ARG
+    assert D.lib.dip_cache_import(None, None, 0, None) == D.DIP_ERR_INVALID_ARG
+
+
 def test_tune_validation(D):
     assert D.lib.dip_tune_gemv(7, 0, 0, 0) == D.DIP_ERR_INVALID_ARG
     assert D.lib.dip_tune_gemv(0, 3, 0, 0) == D.DIP_ERR_INVALID_ARG

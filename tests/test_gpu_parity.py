@@ -159,6 +159,44 @@ def test_cache_init_with_warm_bits(D):
     assert np.array_equal(bits, st.resident) and np.array_equal(stamp, st.stamp)
 
 
+@pytest.mark.parametrize("where", ["device", "pinned", "pageable"])
+def test_cache_export_import_round_trip(D, where):
+    """A checkpointed cache resumes exactly: export, run on, import, and the replayed tokens
+    give the states the oracle gives; the blob layout is [bits | stamp | meta] on 256-byte starts."""
+    n, cap, k = 3000, 1200, 700
+    cache = D.Cache(n, cap)
+    D.dip_cache_init(cache)
+    st = O.CacheState(n=n, capacity=cap)
+    xs = ar1_laplace_stream(10, n, seed=77)
+    masks = [O.topk(np.abs(x), k)[0] for x in xs]
+    for m in masks[:5]:
+        D.dip_cache_update(cache, dev_u32(bits_from_bool(m)))
+        O.cache_update(st, m)
+    nbytes = D.dip_cache_blob_bytes(n)
+    assert D.dip_cache_state_bytes(n) == (4 * ((n + 31) // 32), 4 * n, 4 * D.libdip.DIP_CACHE_META_WORDS)
+    if where == "device":
+        blob = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    else:
+        blob = torch.zeros(nbytes, dtype=torch.uint8, pin_memory=(where == "pinned"))
+    D.dip_cache_export(cache, blob)
+    torch.cuda.synchronize()
+    raw = blob.cpu().numpy()
+    off_stamp = -(-(4 * ((n + 31) // 32)) // 256) * 256
+    assert np.array_equal(bool_from_bits(raw[:4 * ((n + 31) // 32)].view(np.uint32), n), st.resident)
+    assert np.array_equal(raw[off_stamp:off_stamp + 4 * n].view(np.uint32), st.stamp)
+    saved = st.copy()
+    for m in masks[5:]:
+        D.dip_cache_update(cache, dev_u32(bits_from_bool(m)))
+    D.dip_cache_import(cache, blob)
+    st = saved
+    for m in masks[5:8]:
+        D.dip_cache_update(cache, dev_u32(bits_from_bool(m)))
+        O.cache_update(st, m)
+    bits, stamp, meta = _cache_state(D, cache, n)
+    assert np.array_equal(bits, st.resident) and np.array_equal(stamp, st.stamp)
+    assert meta["step"] == st.step and meta["cum_hits"] == st.hits
+
+
 # ------------------------------------------------------------------ gathered GEMV
 SHAPES = [  # (n_in, n_out, k)
     (64, 64, 1), (100, 200, 37), (512, 1536, 256), (1536, 512, 768), (3072, 1024, 1536),
