@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--scheme", default="dip", choices=("dip", "glu", "gate", "up"),
                     help="dip: the headline path; glu / gate / up: the sibling schemes that prune on "
                          "(partial) GLU activations, k = keep ratio of d_ff, no cache")
+    ap.add_argument("--tiered", action="store_true",
+                    help="two-tier residency: the matrices live in pinned host memory, cache-capacity many "
+                         "columns of each in HBM slots; misses cross PCIe (use with --gamma 1.0 / 0.2)")
+    ap.add_argument("--gamma", type=float, default=None, help="cache-aware penalty (1.0 = plain DIP keys)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=24)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -174,6 +178,106 @@ def bench_scheme(a):
     print(json.dumps(out))
 
 
+def bench_tiered(a):
+    """DIP-CA with misses that are really slow: per step, the columns a cache update inserts are
+    copied host -> HBM and the misses that bypass the cache are read over PCIe by the product."""
+    import numpy as np
+    import torch
+
+    import paper_2412_01380_amd as D
+    from workloads import CONFIGS, layer_weights
+
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[a.config]
+    assert cfg.dtype != "int4", "tiers hold f32 / bf16 matrices"
+    r = a.ratio if a.ratio is not None else 0.3
+    frac = a.cache_frac if a.cache_frac is not None else 0.5
+    gamma = a.gamma if a.gamma is not None else cfg.gamma
+    d, f = cfg.d_model, cfg.d_ff
+    k_in, k_mid = cfg.k_in(r), cfg.k_mid(r)
+    C_in, C_mid = int(np.floor(frac * d + 0.5)), int(np.floor(frac * f + 0.5))
+    L = a.layers if a.layers is not None else 4
+    n_tok = cfg.n_tokens
+
+    def pinned(arr):
+        t = torch.from_numpy(arr.view(np.int16))
+        p = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+        p.copy_(t)
+        return p
+
+    mlps, cins, cmids = [], [], []
+    for l in range(L):
+        w = layer_weights(d, f, cfg.seed, l, cfg.dtype)
+        tu, td = D.TieredWeight(pinned(w["ug"]), C_in), D.TieredWeight(pinned(w["d"]), C_mid)
+        ci, cm = D.Cache(d, C_in), D.Cache(f, C_mid)
+        for tw, c in ((tu, ci), (td, cm)):
+            D.dip_cache_init(c)
+            D.dip_tier_init(tw, c, torch.empty(max(256, D.dip_tier_init_workspace_bytes(tw)), dtype=torch.uint8, device="cuda"))
+        mlps.append(D.TieredMlp(tu, td)); cins.append(ci); cmids.append(cm)
+        del w
+    X = np.stack([cfg.tokens(layer=l, n_tokens=n_tok) for l in range(L)], axis=1)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.empty(L, d, dtype=torch.float32, device="cuda")
+    ws = torch.empty(D.dip_tiered_mlp_forward_workspace_bytes(mlps[0], k_in, k_mid), dtype=torch.uint8, device="cuda")
+
+    def run_pass(t):
+        for l in range(L):
+            D.dip_tiered_mlp_forward(mlps[l], Xd[t % n_tok, l], k_in, k_mid, cins[l], cmids[l], gamma, Yd[l], None, ws)
+
+    def lookups():
+        mi = [c.meta_host() for c in cins]
+        mm = [c.meta_host() for c in cmids]
+        return (sum(m["cum_hits"] for m in mi), sum(m["cum_lookups"] for m in mi),
+                sum(m["cum_hits"] for m in mm), sum(m["cum_lookups"] for m in mm))
+
+    passes_w = max(1, (a.warmup + L - 1) // L)
+    passes = max(1, (a.steps + L - 1) // L)
+    steps = passes * L
+    for t in range(passes_w):
+        run_pass(t)
+    torch.cuda.synchronize()
+    h0 = lookups()
+    t0 = time.perf_counter()
+    for t in range(passes):
+        run_pass(passes_w + t)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    h1 = lookups()
+    hit_in, look_in, hit_mid, look_mid = (b - a_ for a_, b in zip(h0, h1))
+    row_ug, row_d = 2 * f * 2, d * 2
+    pcie = (look_in - hit_in) * row_ug + (look_mid - hit_mid) * row_d
+    gathered = cfg.gathered_bytes(r)
+    D.dip_profile_enable(8 * L * min(passes, 64) + 16)
+    for t in range(min(passes, 64)):
+        run_pass(passes_w + passes + t)
+    torch.cuda.synchronize()
+    kinds = {"select_in": 0, "gemv_upgate": 1, "select_mid": 2, "gemv_down": 3, "tier_fill": 6}
+    prof = {kname: D.dip_profile_read(i) for kname, i in kinds.items()}
+    D.dip_profile_disable()
+    ug_ms, ug_n = prof["gemv_upgate"]
+    ug_bytes = 2 * k_in * f * 2
+    ach = ug_bytes / (ug_ms / ug_n * 1e-3) / 1e9
+    out = {
+        "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
+        "value": steps / wall, "unit": "layer-tokens/s", "n_gpus": 1, "steps": steps, "warmup": passes_w * L,
+        "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"two-tier residency on the MLP shape of BASELINE configs[{a.config - 1}]: {cfg.name}, "
+                               f"d_model={d}, d_ff={f}, {cfg.dtype} weights in pinned host memory, "
+                               f"HBM slot cache frac {frac} (C_in={C_in}, C_mid={C_mid}), LRU, gamma {gamma}, "
+                               f"keep ratio {r} (k_in={k_in}, k_mid={k_mid}), batch 1, {L} layers round-robin",
+                   "inputs": cfg.inputs, "weights_dtype": cfg.dtype, "gathered_bytes_per_step": gathered},
+        "end_to_end_GBps": gathered * steps / wall / 1e9,
+        "tier": {"gamma": gamma, "hit_rate_in": hit_in / max(look_in, 1), "hit_rate_mid": hit_mid / max(look_mid, 1),
+                 "pcie_bytes_per_step": pcie / steps, "pcie_GBps": pcie / wall / 1e9},
+        "kernels_us": {kname: v[0] / v[1] * 1e3 for kname, v in prof.items() if v[1]},
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "gemv_kernel (up/gate + SwiGLU), rows from HBM slots or host memory",
+                     "algorithmic_bytes_per_launch": ug_bytes, "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n},
+    }
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -191,6 +295,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if a.scheme != "dip":
         return bench_scheme(a)
+    if a.tiered:
+        return bench_tiered(a)
     torch.cuda.set_device(0)
     cfg = CONFIGS[a.config]
     r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3, 5: 0.3}[a.config]
