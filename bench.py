@@ -41,6 +41,8 @@ def parse():
                     help="two-tier residency: the matrices live in pinned host memory, cache-capacity many "
                          "columns of each in HBM slots; misses cross PCIe (use with --gamma 1.0 / 0.2)")
     ap.add_argument("--gamma", type=float, default=None, help="cache-aware penalty (1.0 = plain DIP keys)")
+    ap.add_argument("--tune", default=None,
+                    help="lanes_per_row,waves,ksplit,unroll override for the gathered GEMV (0 = built-in choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=24)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -293,6 +295,8 @@ def main():
     from workloads import CONFIGS, layer_weights
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if a.tune:
+        D.dip_tune_gemv(*[int(v) for v in a.tune.split(",")])
     if a.scheme != "dip":
         return bench_scheme(a)
     if a.tiered:

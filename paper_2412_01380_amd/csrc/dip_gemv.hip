@@ -20,6 +20,7 @@
 namespace dip {
 
 GemvShape g_gemv_override = {0, 0, 0, 0};
+constexpr int kComputeUnits = 256;   // MI355X
 
 namespace {
 
@@ -597,28 +598,50 @@ int gemv_strips(const GemvShape& s, int dtype, int n_out) {
 }
 
 GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
-    // Defaults from launch-shape sweeps on MI355X (Phi-3-Mini, Llama-3-8B and Phi-3-Medium
-    // shaped layers): 16 lanes per row, 8 wavefronts, 4 rows in flight per lane group, and
-    // enough row splits that a workgroup streams a few hundred rows -- long enough to
-    // amortise its prologue and reduction, short enough to fill 256 compute units.
+    // Defaults from launch-shape sweeps and same-box comparisons on MI355X (Phi-3-Mini,
+    // Llama-3-8B and Phi-3-Medium shaped layers): 8 wavefronts, 4 rows in flight per lane
+    // group, 16 lanes per row (32 for the bundled up/gate matrix when that gives whole
+    // rounds), and row shares of a few hundred rows -- long enough to amortise a workgroup's
+    // prologue and reduction, short enough to fill 256 compute units.
     GemvShape s;
     const bool q4 = dtype == DIP_INT4_G128;   // 32 codes per lane: narrower strips, fewer rows in flight
+    const int epl = elems_per_load(dtype);
     s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : (q4 ? 8 : 16);
     s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
     s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
+    int ks = 0;
+    if (nseg == 2 && !q4 && !g_gemv_override.lpr && !g_gemv_override.ksplit) {
+        // Bundled up/gate: whole rounds of workgroups.  With strips * ksplit just below one
+        // or two times the 256 compute units no unit is left with an extra workgroup while
+        // the others idle (280 workgroups take as long as 512); take the widest strip and
+        // the fewest rounds whose shares come out between 200 and 400 rows.
+        const int lprs[2] = {32, 16};
+        for (int li = 0; li < 2 && !ks; ++li)
+            for (int m = 1; m <= 2 && !ks; ++m) {
+                const int strips = (n_out + lprs[li] * epl - 1) / (lprs[li] * epl);
+                const int cand = kComputeUnits * m / strips;
+                if (cand < 1) continue;
+                const int share = (k + cand - 1) / cand;
+                if (share >= 200 && share <= 400) {
+                    s.lpr = lprs[li];
+                    ks = cand;
+                }
+            }
+    }
     // a bundled strip needs 2*SC lanes for its epilogue
-    const int epl = elems_per_load(dtype);
     while (nseg * s.lpr * epl > s.waves * 64 && s.waves < 16) s.waves *= 2;
     if (g_gemv_override.ksplit) {
         s.ksplit = g_gemv_override.ksplit;
     } else {
-        const int strips = gemv_strips(s, dtype, n_out);
-        // (int4 rows are a quarter of the bytes and the reduction costs the same: longer shares)
-        const int rows_per_wg = q4 ? (nseg == 2 ? 768 : 640) : (nseg == 2 ? 384 : 512);
-        int ks = (k + rows_per_wg / 2) / rows_per_wg;
-        if (ks < 1) ks = 1;
-        const int min_wgs = q4 ? 128 : 192;
-        if (strips * ks < min_wgs) ks = (min_wgs + strips - 1) / strips;
+        if (!ks) {
+            const int strips = gemv_strips(s, dtype, n_out);
+            // (int4 rows are a quarter of the bytes and the reduction costs the same: longer shares)
+            const int rows_per_wg = q4 ? (nseg == 2 ? 768 : 640) : (nseg == 2 ? 384 : 512);
+            ks = (k + rows_per_wg / 2) / rows_per_wg;
+            if (ks < 1) ks = 1;
+            const int min_wgs = q4 ? 128 : 192;
+            if (strips * ks < min_wgs) ks = (min_wgs + strips - 1) / strips;
+        }
         // but keep at least one full iteration of rows per workgroup
         const int rows_per_iter = s.waves * (64 / s.lpr) * s.unroll;
         while (ks > 1 && k / ks < rows_per_iter) --ks;
