@@ -417,12 +417,16 @@ def main():
     # ---- per-kernel durations from HIP events bound to the dispatches ---------------------
     if not a.no_kernel_events:
         n_prof = min(passes, max(1, 2048 // L))
-        D.dip_profile_enable(4 * L * n_prof + 16)
+        D.dip_profile_enable(5 * L * n_prof + 16)
         for t in range(n_prof):
             run_pass(passes_w + passes + t)
         torch.cuda.synchronize()
         prof = {k: D.dip_profile_read(i) for i, k in
                 enumerate(("select_in", "gemv_upgate", "select_mid", "gemv_down"))}
+        try:
+            prof["cache_update_tail"] = D.dip_profile_read(7)   # one per stack call, when caches are on
+        except D.DipError:
+            pass
         D.dip_profile_disable()
         out["kernels_us"] = {k: (v[0] / v[1] * 1e3 if v[1] else None) for k, v in prof.items()}
         ug_ms, ug_n = prof["gemv_upgate"]

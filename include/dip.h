@@ -388,7 +388,8 @@ int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, i
 #define DIP_KERNEL_GEMV_DENSE 4  /* dense first product of gate / up pruning                */
 #define DIP_KERNEL_ROWDOT 5      /* row-gathered dot products                               */
 #define DIP_KERNEL_TIER_FILL 6   /* host -> HBM copies of the columns a cache update inserted  */
-#define DIP_KERNEL_KINDS 7
+#define DIP_KERNEL_CACHE_UPDATE 7 /* a cache update launched on its own (end of a forward call) */
+#define DIP_KERNEL_KINDS 8
 int32_t dip_profile_enable(int32_t max_launches);
 int32_t dip_profile_read(int32_t kind, double* total_ms /* host */, int32_t* launches /* host */);
 int32_t dip_profile_disable(void);

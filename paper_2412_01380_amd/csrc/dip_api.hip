@@ -95,8 +95,16 @@ struct ForwardPlan {
     int d, f;
     GemvShape ug, dn;
     int strips_ug, strips_dn;
-    size_t off_idx1, off_val1, off_h, off_idx2, off_val2, off_part_ug, off_part_dn, off_cnt;
+    size_t off_mask1, off_mask2[2], off_idx1, off_val1, off_h, off_idx2, off_val2, off_part_ug, off_part_dn, off_cnt;
     size_t total;
+};
+
+// A cache update that no kernel of the current token waits for: it is handed to the next
+// selection launch as work for a second workgroup (or launched on its own at the end).
+struct PendingUpdate {
+    bool active = false;
+    int parity = 0;       // which of the two point-2 mask buffers the next layer writes
+    SelectParams p;
 };
 
 ForwardPlan plan_forward(const dip_mlp* mlp, int k_in, int k_mid) {
@@ -109,6 +117,12 @@ ForwardPlan plan_forward(const dip_mlp* mlp, int k_in, int k_mid) {
     pl.strips_dn = gemv_strips(pl.dn, mlp->w_d.dtype, pl.d);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    // The mask buffers sit at the same place for every layer shape, and point 2 has two of
+    // them used in turn: the deferred cache update of one layer reads its mask while the
+    // next layer (maybe of another shape, with another plan) writes its own.
+    pl.off_mask1 = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
+    pl.off_mask2[0] = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
+    pl.off_mask2[1] = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
     pl.off_idx1 = take(sizeof(int32_t) * k_in);
     pl.off_val1 = take(sizeof(float) * k_in);
     pl.off_h = take(sizeof(float) * pl.f);
@@ -138,9 +152,22 @@ int32_t validate_mlp(const dip_mlp* mlp, int k_in, int k_mid) {
     return DIP_OK;
 }
 
+// Launch order for one token of one layer with caches at both points:
+//   scores + top-K at point 1
+//   gathered up/gate product
+//   [scores + top-K at point 2 | cache update of point 1 | cache update of point 2 left over
+//    from the previous layer]          (three workgroups of one launch)
+//   gathered down product
+// and the cache update of point 2 is left pending.  A cache is scored with its state before
+// this token (the update of the same cache always comes in a later launch), and two launches
+// that touch the same cache are ordered by the stream.
 int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, int k_in, int k_mid,
                     const dip_cache* cin, const dip_cache* cmid, float gamma, float* y,
-                    const dip_debug* dbg, char* ws, hipStream_t stream, bool dense_in = false) {
+                    const dip_debug* dbg, char* ws, hipStream_t stream, PendingUpdate& pending,
+                    bool dense_in = false) {
+    uint32_t* mask1 = reinterpret_cast<uint32_t*>(ws + pl.off_mask1);
+    uint32_t* mask2 = reinterpret_cast<uint32_t*>(ws + pl.off_mask2[pending.parity]);
+    pending.parity ^= 1;
     int32_t* idx1 = reinterpret_cast<int32_t*>(ws + pl.off_idx1);
     float* val1 = reinterpret_cast<float*>(ws + pl.off_val1);
     float* h = reinterpret_cast<float*>(ws + pl.off_h);
@@ -153,6 +180,17 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     if (dbg && dbg->idx_in) idx1 = dbg->idx_in;
     if (dbg && dbg->idx_mid) idx2 = dbg->idx_mid;
     if (dbg && dbg->h) h = dbg->h;
+    if (dbg && dbg->mask_in) mask1 = dbg->mask_in;
+    if (dbg && dbg->mask_mid) mask2 = dbg->mask_mid;
+
+    auto update_of = [](const dip_cache* c, const uint32_t* mask) {
+        SelectParams u;
+        std::memset(&u, 0, sizeof(u));
+        u.n = c->n; u.k = 1; u.mask_in = mask;
+        u.c_bits = c->bits; u.c_stamp = c->stamp; u.c_meta = c->meta;
+        u.capacity = c->capacity; u.policy = c->policy;
+        return u;
+    };
 
     int32_t st = DIP_OK;
     if (dense_in) {
@@ -160,17 +198,15 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
         st = check_hip(launch_zero_u32(cnt_ug, pl.strips_ug + pl.strips_dn, stream), "counter reset");
         if (st) return st;
     } else {
-        // point 1: scores, m1, cache update
+        // point 1: scores and m1
         SelectParams s1;
         std::memset(&s1, 0, sizeof(s1));
         s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
         s1.s_out = dbg ? dbg->s_in : nullptr;
-        s1.mask_out = dbg ? dbg->mask_in : nullptr;
+        s1.mask_out = (cin || dbg) ? mask1 : nullptr;
+        if (!cin && dbg && !dbg->mask_in) s1.mask_out = nullptr;
         s1.idx_out = idx1; s1.val_out = val1;
-        if (cin) {
-            s1.score_bits = cin->bits; s1.c_bits = cin->bits; s1.c_stamp = cin->stamp; s1.c_meta = cin->meta;
-            s1.capacity = cin->capacity; s1.policy = cin->policy;
-        }
+        if (cin) s1.score_bits = cin->bits;
         s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
         st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
         if (st) return st;
@@ -187,19 +223,25 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
     if (st) return st;
 
-    // point 2
+    // point 2: scores and m2, next to the cache update of point 1
     SelectParams s2;
     std::memset(&s2, 0, sizeof(s2));
     s2.v = h; s2.n = pl.f; s2.k = k_mid; s2.gamma = gamma;
     s2.s_out = dbg ? dbg->s_mid : nullptr;
-    s2.mask_out = dbg ? dbg->mask_mid : nullptr;
+    s2.mask_out = (cmid || (dbg && dbg->mask_mid)) ? mask2 : nullptr;
     s2.idx_out = idx2; s2.val_out = val2;
-    if (cmid) {
-        s2.score_bits = cmid->bits; s2.c_bits = cmid->bits; s2.c_stamp = cmid->stamp; s2.c_meta = cmid->meta;
-        s2.capacity = cmid->capacity; s2.policy = cmid->policy;
+    if (cmid) s2.score_bits = cmid->bits;
+    SelectParams u1;
+    const SelectParams* ride[2] = {nullptr, nullptr};
+    int n_ride = 0;
+    if (cin && !dense_in) {
+        u1 = update_of(cin, mask1);
+        ride[n_ride++] = &u1;
     }
-    st = check_hip(launch_select(s2, stream, DIP_KERNEL_SELECT_MID), "select (point 2)");
+    if (pending.active) ride[n_ride++] = &pending.p;
+    st = check_hip(launch_select(s2, stream, DIP_KERNEL_SELECT_MID, ride[0], ride[1]), "select (point 2)");
     if (st) return st;
+    pending.active = false;
 
     // gathered down GEMV
     GemvParams g2;
@@ -208,7 +250,19 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     g2.scales = static_cast<const uint16_t*>(mlp->w_d.scales); g2.scale_stride = mlp->w_d.n_out / 128; g2.dtype = mlp->w_d.dtype;
     g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.idx = idx2; g2.val = val2; g2.k = k_mid; g2.out = y;
     g2.partial = part_dn; g2.counters = cnt_dn;
-    return check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+    st = check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+    if (st) return st;
+    if (cmid) {
+        pending.p = update_of(cmid, mask2);
+        pending.active = true;
+    }
+    return DIP_OK;
+}
+
+int32_t flush_pending(PendingUpdate& pending, hipStream_t stream) {
+    if (!pending.active) return DIP_OK;
+    pending.active = false;
+    return check_hip(launch_select(pending.p, stream, DIP_KERNEL_CACHE_UPDATE), "cache update (point 2)");
 }
 
 }  // namespace
@@ -395,15 +449,20 @@ static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const floa
     if (!ws || ws_bytes < need || !aligned(ws, 256))
         return fail(DIP_ERR_WORKSPACE, "forward: workspace must be 256-aligned and >= %zu bytes", need);
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    PendingUpdate pending;
     for (int l = 0; l < n_layers; ++l) {
         const ForwardPlan pl = plan_forward(&mlps[l], k_in, k_mid);
         int32_t st = forward_one(&mlps[l], pl, x + (int64_t)l * x_stride, k_in, k_mid,
                                  caches_in ? &caches_in[l] : nullptr,
                                  caches_mid ? &caches_mid[l] : nullptr, gamma,
-                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs, dense_in);
-        if (st) return st;
+                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs, pending,
+                                 dense_in);
+        if (st) {
+            flush_pending(pending, hs);   // keep the caches consistent with what was launched
+            return st;
+        }
     }
-    return DIP_OK;
+    return flush_pending(pending, hs);
 }
 
 int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,

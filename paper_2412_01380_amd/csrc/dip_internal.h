@@ -66,7 +66,9 @@ struct SelectParams {
     int64_t words_row_stride;
 };
 
-hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind);
+// `second`, `third`: independent work for further workgroups of the same launch (no batch rows then)
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind,
+                         const SelectParams* second = nullptr, const SelectParams* third = nullptr);
 
 struct CacheInitParams {
     uint32_t* bits;

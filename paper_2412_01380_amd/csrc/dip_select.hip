@@ -330,8 +330,13 @@ __device__ __forceinline__ void store_ballot_words(uint32_t* words, int nwords, 
 }
 
 template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, SelectParams second, SelectParams third) {
     __shared__ SelShared sh;
+    // A launch may carry independent pieces of work for further workgroups (blockIdx.y = 1, 2):
+    // cache updates of earlier pruning points, which nothing in this token waits for, next
+    // to this point's scores and top-K.
+    if (blockIdx.y == 1) p = second;
+    if (blockIdx.y == 2) p = third;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwords = (p.n + 31) >> 5;
     int phase = 0;
@@ -633,31 +638,48 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 }
 
 template <int ITEMS>
-hipError_t launch_items(const SelectParams& p, hipStream_t stream, int prof_kind) {
-    return launch_timed(select_kernel<ITEMS>, dim3(p.rows > 1 ? p.rows : 1), dim3(kSelThreads), stream, prof_kind, p);
+hipError_t launch_items(const SelectParams& p, const SelectParams* second, const SelectParams* third,
+                        hipStream_t stream, int prof_kind) {
+    const dim3 grid(p.rows > 1 ? p.rows : 1, third ? 3 : (second ? 2 : 1));
+    const SelectParams& q = second ? *second : p;
+    const SelectParams& r = third ? *third : p;
+    hipEvent_t e0, e1;
+    if (prof_kind >= 0 && prof_next(prof_kind, &e0, &e1)) {
+        hipExtLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, e0, e1, 0, p, q, r);
+    } else {
+        hipLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, p, q, r);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind) {
-    const int items = (p.n + kSelThreads - 1) / kSelThreads;
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind, const SelectParams* second,
+                         const SelectParams* third) {
+    // all pieces of work run the same instantiation: the one that fits the longest vector
+    if (third && !second) return hipErrorInvalidValue;
+    if (second && (p.rows > 1 || second->rows > 1 || (third && third->rows > 1))) return hipErrorInvalidValue;
+    int n = p.n;
+    if (second && second->n > n) n = second->n;
+    if (third && third->n > n) n = third->n;
+    const int items = (n + kSelThreads - 1) / kSelThreads;
     switch (items) {
-        case 1: return launch_items<1>(p, stream, prof_kind);
-        case 2: return launch_items<2>(p, stream, prof_kind);
-        case 3: return launch_items<3>(p, stream, prof_kind);
-        case 4: return launch_items<4>(p, stream, prof_kind);
-        case 5: return launch_items<5>(p, stream, prof_kind);
-        case 6: return launch_items<6>(p, stream, prof_kind);
-        case 7: case 8: return launch_items<8>(p, stream, prof_kind);
-        case 9: case 10: return launch_items<10>(p, stream, prof_kind);
-        case 11: case 12: return launch_items<12>(p, stream, prof_kind);
-        case 13: case 14: return launch_items<14>(p, stream, prof_kind);
-        case 15: case 16: return launch_items<16>(p, stream, prof_kind);
-        case 17: case 18: return launch_items<18>(p, stream, prof_kind);
-        case 19: case 20: return launch_items<20>(p, stream, prof_kind);
-        case 21: case 22: case 23: case 24: return launch_items<24>(p, stream, prof_kind);
-        case 25: case 26: case 27: case 28: return launch_items<28>(p, stream, prof_kind);
-        default: return launch_items<32>(p, stream, prof_kind);
+        case 1: return launch_items<1>(p, second, third, stream, prof_kind);
+        case 2: return launch_items<2>(p, second, third, stream, prof_kind);
+        case 3: return launch_items<3>(p, second, third, stream, prof_kind);
+        case 4: return launch_items<4>(p, second, third, stream, prof_kind);
+        case 5: return launch_items<5>(p, second, third, stream, prof_kind);
+        case 6: return launch_items<6>(p, second, third, stream, prof_kind);
+        case 7: case 8: return launch_items<8>(p, second, third, stream, prof_kind);
+        case 9: case 10: return launch_items<10>(p, second, third, stream, prof_kind);
+        case 11: case 12: return launch_items<12>(p, second, third, stream, prof_kind);
+        case 13: case 14: return launch_items<14>(p, second, third, stream, prof_kind);
+        case 15: case 16: return launch_items<16>(p, second, third, stream, prof_kind);
+        case 17: case 18: return launch_items<18>(p, second, third, stream, prof_kind);
+        case 19: case 20: return launch_items<20>(p, second, third, stream, prof_kind);
+        case 21: case 22: case 23: case 24: return launch_items<24>(p, second, third, stream, prof_kind);
+        case 25: case 26: case 27: case 28: return launch_items<28>(p, second, third, stream, prof_kind);
+        default: return launch_items<32>(p, second, third, stream, prof_kind);
     }
 }
 
