@@ -271,6 +271,8 @@ int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in,
  * stack): layer l reads x + l * x_stride and writes y_out + l * y_stride (strides in
  * floats).  mlps / caches_in / caches_mid are host arrays of n_layers descriptors; the
  * cache arrays may be NULL (DIP) .  All layers share one workspace sized for the largest.
+ * Every layer needs cache descriptors of its own: the update of one layer's point-2 cache
+ * runs next to the following layer's kernels.
  */
 int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,
                                      int64_t x_stride, int32_t k_in, int32_t k_mid,
