@@ -428,6 +428,51 @@ def test_stack_call_equals_per_layer_calls(D):
             assert np.array_equal(host_u32(cmids[l].stamp), host_u32(cmids2[l].stamp))
 
 
+@pytest.mark.parametrize("which", ["both", "mid_only", "in_only"])
+def test_stack_of_mixed_shapes_with_deferred_cache_updates(D, which):
+    """Layers of different d_ff in one stack call (each with its own workspace plan), caches at
+    both points or at one: the cache updates that ride along later launches must leave every
+    cache in the state the oracle reaches, token after token, and y must equal per-layer calls."""
+    d, k_in = 512, 160
+    ffs, k_mids = [1536, 2304, 1024, 3200], [400, 700, 256, 1000]
+    L = len(ffs)
+    layers = [_setup_layer(D, d, ffs[l], "f32", 13, l, k_in, k_mids[l]) for l in range(L)]
+    use_in, use_mid = which != "mid_only", which != "in_only"
+    # one k_mid per call: use the smallest so that it is valid for every layer
+    k_mid = min(k_mids)
+    ws = workspace(max(D.dip_swiglu_mlp_forward_workspace_bytes(l["mlp"], k_in, k_mid) for l in layers))
+    cins = [D.Cache(d, 256) for _ in range(L)] if use_in else None
+    cmids = [D.Cache(ffs[l], ffs[l] // 2) for l in range(L)] if use_mid else None
+    cins2 = [D.Cache(d, 256) for _ in range(L)]
+    cmids2 = [D.Cache(ffs[l], ffs[l] // 2) for l in range(L)]
+    for c in (cins or []) + (cmids or []) + cins2 + cmids2:
+        D.dip_cache_init(c)
+    oin = [O.CacheState(n=d, capacity=256) for _ in range(L)]
+    omid = [O.CacheState(n=ffs[l], capacity=ffs[l] // 2) for l in range(L)]
+    stack = D.MlpStack([l["mlp"] for l in layers], cins, cmids)
+    xs = ar1_laplace_stream(L * 4, d, seed=7).reshape(4, L, d)
+    X = dev_f32(xs)
+    Y = torch.empty(L, d, dtype=torch.float32, device="cuda")
+    for t in range(4):
+        D.dip_swiglu_mlp_forward_stack(stack, X[t], d, k_in, k_mid, 0.2, Y, d, ws)
+        torch.cuda.synchronize()
+        for l in range(L):
+            w = layers[l]
+            D.dip_swiglu_mlp_forward(w["mlp"], X[t, l], k_in, k_mid, cins2[l] if use_in else None,
+                                     cmids2[l] if use_mid else None, 0.2, w["y"], w["dbg"], ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(Y[l].cpu().numpy().view(np.uint32), w["y"].cpu().numpy().view(np.uint32))
+            # the oracle, driven by the GPU's masks (stage replay), gives the cache states
+            if use_in:
+                O.cache_update(oin[l], bool_from_bits(host_u32(w["dbg"].mask_in), d))
+                assert np.array_equal(bool_from_bits(host_u32(cins[l].bits), d), oin[l].resident)
+                assert np.array_equal(cins[l].stamp.cpu().numpy().view(np.uint32), oin[l].stamp)
+            if use_mid:
+                O.cache_update(omid[l], bool_from_bits(host_u32(w["dbg"].mask_mid), ffs[l]))
+                assert np.array_equal(bool_from_bits(host_u32(cmids[l].bits), ffs[l]), omid[l].resident)
+                assert np.array_equal(cmids[l].stamp.cpu().numpy().view(np.uint32), omid[l].stamp)
+
+
 # ------------------------------------------------------------------ int4-g128 weights (batch 1)
 @pytest.mark.parametrize("n_in,n_out,k", [(64, 128, 1), (300, 256, 111), (1536, 512, 768), (777, 1152, 300)])
 def test_gathered_gemv_int4_matches_oracle(D, n_in, n_out, k):
