@@ -560,6 +560,10 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
          mask_mid_out ? mask_mid_out : reinterpret_cast<uint32_t*>(base + pl.off_m2),
          reinterpret_cast<uint32_t*>(base + pl.off_u2), reinterpret_cast<int32_t*>(base + pl.off_idx2),
          reinterpret_cast<float*>(base + pl.off_val2), cnt + 1, DIP_KERNEL_SELECT_MID}};
+    // The cache update of a point is not needed by anything in this step: the one of point 1
+    // rides along the row selection of point 2, the one of point 2 is launched at the end.
+    SelectParams deferred;
+    bool have_deferred = false;
     for (int pt = 0; pt < 2; ++pt) {
         const Point& q = pts[pt];
         // per-row scores and masks (state of the cache from before the step)
@@ -568,7 +572,10 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         sp.v = q.v; sp.n = q.n; sp.k = q.k; sp.gamma = gamma;
         sp.score_bits = q.cache ? q.cache->bits : nullptr;
         sp.mask_out = q.masks; sp.rows = batch; sp.v_row_stride = q.n; sp.words_row_stride = q.words;
-        if ((st = check_hip(launch_select(sp, hs, q.kind), "forward_batched: select"))) return st;
+        if ((st = check_hip(launch_select(sp, hs, q.kind, have_deferred ? &deferred : nullptr),
+                            "forward_batched: select")))
+            return st;
+        have_deferred = false;
         // union of the row masks, its index list and the row multipliers
         UnionParams up;
         std::memset(&up, 0, sizeof(up));
@@ -577,12 +584,11 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         if ((st = check_hip(launch_union(up, hs), "forward_batched: union"))) return st;
         // one cache update with the union mask
         if (q.cache) {
-            SelectParams cp;
-            std::memset(&cp, 0, sizeof(cp));
-            cp.n = q.n; cp.k = 1; cp.mask_in = q.uwords;
-            cp.c_bits = q.cache->bits; cp.c_stamp = q.cache->stamp; cp.c_meta = q.cache->meta;
-            cp.capacity = q.cache->capacity; cp.policy = q.cache->policy;
-            if ((st = check_hip(launch_select(cp, hs, -1), "forward_batched: cache update"))) return st;
+            std::memset(&deferred, 0, sizeof(deferred));
+            deferred.n = q.n; deferred.k = 1; deferred.mask_in = q.uwords;
+            deferred.c_bits = q.cache->bits; deferred.c_stamp = q.cache->stamp; deferred.c_meta = q.cache->meta;
+            deferred.capacity = q.cache->capacity; deferred.policy = q.cache->policy;
+            have_deferred = true;
         }
         // gathered product for all rows, then the reduction with its epilogue
         const dip_weight& w = pt == 0 ? mlp->w_ug : mlp->w_d;
@@ -603,6 +609,8 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         rp.out = pt == 0 ? H : Y; rp.out_stride = pt == 0 ? pl.f : pl.d;
         if ((st = check_hip(launch_batched_reduce(rp, hs), "forward_batched: reduction"))) return st;
     }
+    if (have_deferred)
+        return check_hip(launch_select(deferred, hs, DIP_KERNEL_CACHE_UPDATE), "forward_batched: cache update");
     return DIP_OK;
 }
 

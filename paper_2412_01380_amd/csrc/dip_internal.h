@@ -66,7 +66,7 @@ struct SelectParams {
     int64_t words_row_stride;
 };
 
-// `second`, `third`: independent work for further workgroups of the same launch (no batch rows then)
+// `second`, `third`: independent single-row work for further workgroups of the same launch
 hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind,
                          const SelectParams* second = nullptr, const SelectParams* third = nullptr);
 

@@ -337,6 +337,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
     // to this point's scores and top-K.
     if (blockIdx.y == 1) p = second;
     if (blockIdx.y == 2) p = third;
+    if (blockIdx.y > 0 && blockIdx.x > 0) return;   // the extra work is never a batch of rows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwords = (p.n + 31) >> 5;
     int phase = 0;
@@ -658,7 +659,7 @@ hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kin
                          const SelectParams* third) {
     // all pieces of work run the same instantiation: the one that fits the longest vector
     if (third && !second) return hipErrorInvalidValue;
-    if (second && (p.rows > 1 || second->rows > 1 || (third && third->rows > 1))) return hipErrorInvalidValue;
+    if ((second && second->rows > 1) || (third && third->rows > 1)) return hipErrorInvalidValue;
     int n = p.n;
     if (second && second->n > n) n = second->n;
     if (third && third->n > n) n = third->n;
