@@ -30,8 +30,11 @@ template <typename WT>
 struct Elem;
 struct q4_t {};  // tag: signed 4-bit codes, one fp16 scale per 128 consecutive elements of a row
 
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
 template <>
 struct Elem<float> {
+    typedef u32x4 raw_t;
     static constexpr int kPerLoad = 4;
     static constexpr int kBits = 32;
     static constexpr bool kScaled = false;
@@ -44,6 +47,7 @@ struct Elem<float> {
 };
 template <>
 struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
+    typedef u32x4 raw_t;
     static constexpr int kPerLoad = 8;
     static constexpr int kBits = 16;
     static constexpr bool kScaled = false;
@@ -65,6 +69,7 @@ struct Elem<q4_t> {
     // turns the two's-complement code q into q + 8 in [0, 15]; masking even and odd nibbles
     // apart leaves them as bytes, which convert to float in one instruction each.  The
     // caller removes the offset: sum (q + 8) m - 8 sum m.
+    typedef u32x4 raw_t;
     static constexpr int kPerLoad = 32;
     static constexpr int kBits = 4;
     static constexpr bool kScaled = true;
@@ -86,6 +91,34 @@ struct Elem<q4_t> {
     }
 };
 
+struct q4n_t {};  // tag: the same 4-bit format read 8 bytes (16 codes) per lane
+template <>
+struct Elem<q4n_t> {
+    // The column-gathered product keeps one accumulator per code and output segment in
+    // registers; with 32 codes per lane that is 64 accumulators and 163 registers, one
+    // workgroup per compute unit, and every latency of a workgroup's prologue and reduction
+    // is exposed (about 8 us per workgroup).  Half the codes per lane halve the
+    // accumulators, and two to three workgroups share a compute unit.
+    typedef u32x2 raw_t;
+    static constexpr int kPerLoad = 16;
+    static constexpr int kBits = 4;
+    static constexpr bool kScaled = true;
+    __device__ static __forceinline__ void widen(const u32x2& q, float (&f)[16]) {
+        const uint32_t w[2] = {q.x, q.y};
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t o = w[i] ^ 0x88888888u;
+            uint32_t ev = o & 0x0f0f0f0fu, od = (o >> 4) & 0x0f0f0f0fu;
+            asm volatile("" : "+v"(ev), "+v"(od));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f[i * 8 + 2 * b] = (float)((ev >> (8 * b)) & 0xffu);
+                f[i * 8 + 2 * b + 1] = (float)((od >> (8 * b)) & 0xffu);
+            }
+        }
+    }
+};
+
 __device__ __forceinline__ float half_bits_to_float(uint16_t h) {
     _Float16 v;
     __builtin_memcpy(&v, &h, 2);
@@ -94,6 +127,10 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h) {
 
 __device__ __forceinline__ u32x4 load16(const char* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+template <typename RAW>
+__device__ __forceinline__ RAW load_raw(const char* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const RAW*>(p));
 }
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + expf(-g)); }
@@ -189,7 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
 
     if (n_full > 0) fetch_full(t0);
     for (int it = 0; it < n_full; ++it) {
-        u32x4 q[UNROLL][NSEG];
+        typename Elem<WT>::raw_t q[UNROLL][NSEG];
         uint16_t sc[UNROLL][NSEG];
         float xc[UNROLL];
 #pragma unroll
@@ -199,7 +236,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
             xc[u] = xv[u];
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
-                q[u][s] = load16(src + off + s * seg_bytes);
+                q[u][s] = load_raw<typename Elem<WT>::raw_t>(src + off + s * seg_bytes);
                 if constexpr (Elem<WT>::kScaled)
                     sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
             }
@@ -224,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
     }
     // Tail: fewer than ROWS_PER_ITER rows are left; rows past the end are skipped.
     if (col_ok && t0 < ke) {
-        u32x4 q[UNROLL][NSEG];
+        typename Elem<WT>::raw_t q[UNROLL][NSEG];
         uint16_t sc[UNROLL][NSEG];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -246,11 +283,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
         for (int u = 0; u < UNROLL; ++u) {
 #pragma unroll
             for (int s = 0; s < NSEG; ++s) {
-                q[u][s] = u32x4{0u, 0u, 0u, 0u};
+                q[u][s] = typename Elem<WT>::raw_t{};
                 sc[u][s] = 0;
                 if (row[u] >= 0) {
                     const char* src = ((alt >> u) & 1u) ? abase : wbase;
-                    q[u][s] = load16(src + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
+                    q[u][s] = load_raw<typename Elem<WT>::raw_t>(src + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
                     if constexpr (Elem<WT>::kScaled)
                         sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
                 }
@@ -589,7 +626,7 @@ hipError_t launch_lpr(const GemvParams& p, const GemvShape& s, hipStream_t strea
 
 }  // namespace
 
-static int elems_per_load(int dtype) { return dtype == DIP_F32 ? 4 : (dtype == DIP_BF16 ? 8 : 32); }
+static int elems_per_load(int dtype) { return dtype == DIP_F32 ? 4 : (dtype == DIP_BF16 ? 8 : 16); }
 
 int gemv_strips(const GemvShape& s, int dtype, int n_out) {
     const int epl = elems_per_load(dtype);
@@ -604,29 +641,40 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     // rounds), and row shares of a few hundred rows -- long enough to amortise a workgroup's
     // prologue and reduction, short enough to fill 256 compute units.
     GemvShape s;
-    const bool q4 = dtype == DIP_INT4_G128;   // 32 codes per lane: narrower strips, fewer rows in flight
+    const bool q4 = dtype == DIP_INT4_G128;
     const int epl = elems_per_load(dtype);
-    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : (q4 ? 8 : 16);
+    s.lpr = g_gemv_override.lpr ? g_gemv_override.lpr : 16;
     s.waves = g_gemv_override.waves ? g_gemv_override.waves : 8;
     s.unroll = g_gemv_override.unroll ? g_gemv_override.unroll : 4;
     int ks = 0;
-    if (nseg == 2 && !q4 && !g_gemv_override.lpr && !g_gemv_override.ksplit) {
-        // Bundled up/gate: whole rounds of workgroups.  With strips * ksplit just below one
-        // or two times the 256 compute units no unit is left with an extra workgroup while
-        // the others idle (280 workgroups take as long as 512); take the widest strip and
-        // the fewest rounds whose shares come out between 200 and 400 rows.
-        const int lprs[2] = {32, 16};
-        for (int li = 0; li < 2 && !ks; ++li)
-            for (int m = 1; m <= 2 && !ks; ++m) {
-                const int strips = (n_out + lprs[li] * epl - 1) / (lprs[li] * epl);
-                const int cand = kComputeUnits * m / strips;
-                if (cand < 1) continue;
-                const int share = (k + cand - 1) / cand;
-                if (share >= 200 && share <= 400) {
-                    s.lpr = lprs[li];
-                    ks = cand;
-                }
+    // Whole rounds of workgroups: with strips * ksplit just below one or two times the 256
+    // compute units no unit is left with an extra workgroup while the others idle (280
+    // workgroups take as long as 512).  Take the fewest rounds whose row shares fall into
+    // the given range.
+    auto whole_rounds = [&](int lpr, int min_share, int max_share) {
+        const int strips = (n_out + lpr * epl - 1) / (lpr * epl);
+        for (int m = 1; m <= 2; ++m) {
+            const int cand = kComputeUnits * m / strips;
+            if (cand < 1) continue;
+            const int share = (k + cand - 1) / cand;
+            if (share >= min_share && share <= max_share) return cand;
+        }
+        return 0;
+    };
+    if (!g_gemv_override.lpr && !g_gemv_override.ksplit) {
+        if (q4) {
+            // 4-bit rows are a quarter of the bytes while a workgroup's fixed costs (prologue,
+            // 32 or 64 accumulators through the cross-lane reduction, the ticket protocol) are
+            // the same: longer shares
+            ks = whole_rounds(16, 256, 640);
+        } else if (nseg == 2) {
+            // bundled up/gate: the widest strip whose shares come out between 200 and 400 rows
+            const int lprs[2] = {32, 16};
+            for (int li = 0; li < 2 && !ks; ++li) {
+                ks = whole_rounds(lprs[li], 200, 400);
+                if (ks) s.lpr = lprs[li];
             }
+        }
     }
     // a bundled strip needs 2*SC lanes for its epilogue
     while (nseg * s.lpr * epl > s.waves * 64 && s.waves < 16) s.waves *= 2;
@@ -657,7 +705,7 @@ hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t str
     p.rows_per_split = ((p.k + s.ksplit - 1) / s.ksplit + 7) / 8 * 8;   // keeps vector index loads aligned
     if (p.dtype == DIP_F32) return launch_lpr<float>(p, s, stream, pk);
     if (p.dtype == DIP_BF16) return launch_lpr<uint16_t>(p, s, stream, pk);
-    if (p.dtype == DIP_INT4_G128) return launch_lpr<q4_t>(p, s, stream, pk);
+    if (p.dtype == DIP_INT4_G128) return launch_lpr<q4n_t>(p, s, stream, pk);
     return hipErrorInvalidValue;
 }
 
