@@ -142,16 +142,19 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t want, Se
 // many keys equal to T belong to the k largest.  Keys that must not take part are 0 and
 // the caller guarantees that at least k keys are larger than 0 or that zero keys at the
 // highest indices are harmless (padding).  Requires k >= 1.
+// `hist_is_zero`: the caller has cleared sh.hist and a barrier lies between that and this call.
 template <int ITEMS, bool SKIP_ZERO>
 __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS], uint32_t k,
                                                      SelShared& sh, int& phase, uint32_t& T,
-                                                     uint32_t& need) {
+                                                     uint32_t& need, bool hist_is_zero = false) {
     const int tid = threadIdx.x, lane = tid & 63;
     uint32_t* histA = sh.hist;
     uint32_t* histB = sh.hist + kBinsA;
     uint32_t* histC = sh.hist + kBinsA + kBinsB;
-    for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) sh.hist[b] = 0u;
-    __syncthreads();
+    if (!hist_is_zero) {
+        for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) sh.hist[b] = 0u;
+        __syncthreads();
+    }
 
     // digit 1: bits 31..20, every key
 #pragma unroll
@@ -362,6 +365,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
             if (p.v) v[j] = p.v[i];
         }
     }
+    // the radix histograms are cleared while the loads above are on their way
+    if (!p.mask_in && !p.scores_only) {
+        for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) sh.hist[b] = 0u;
+        __syncthreads();
+    }
     // residency and (when given) mask words: one per lane, then bit tests out of LDS
     const uint32_t* rb = p.c_bits ? p.c_bits : p.score_bits;
     if (rb || p.mask_in) {
@@ -417,7 +425,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) key[j] <<= 1;
         uint32_t T, need;
-        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need);
+        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need, true);
         const int pre = (int)tile_prefix_eq_gt<ITEMS>(key, T, sh, phase);
         const bool want_words = p.mask_out || p.c_bits;
         // a wave ballot over slot j is two words of the mask: lane 2j keeps the low word and
