@@ -29,6 +29,8 @@ def D():
     ("f32", 96, 64, 96), ("f32", 300, 1000, 123), ("f32", 1536, 512, 768),
     ("bf16", 200, 72, 57), ("bf16", 8192, 3072, 4096), ("bf16", 1000, 5120, 1), ("bf16", 777, 8200, 300),
     ("int4", 256, 128, 100), ("int4", 1984, 5120, 900), ("int4", 640, 3072, 640),
+    # rows longer than 16384 floats of x: more than 64 KB of LDS, several chunks per row
+    ("f32", 64, 20480, 64), ("bf16", 128, 32768, 77),
 ])
 def test_rowdot_matches_oracle(D, fmt, n_rows, n_cols, k):
     # a neuron-major matrix [n_rows][n_cols] is what layer_weights calls 'd' with d_ff = n_rows
