@@ -18,7 +18,7 @@
 #include "dip_internal.h"
 
 #ifndef SEL_WRITELANE
-#define SEL_WRITELANE 0
+#define SEL_WRITELANE 1
 #endif
 
 namespace dip {
@@ -146,7 +146,8 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t want, Se
 template <int ITEMS, bool SKIP_ZERO>
 __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS], uint32_t k,
                                                      SelShared& sh, int& phase, uint32_t& T,
-                                                     uint32_t& need, bool hist_is_zero = false) {
+                                                     uint32_t& need, bool hist_is_zero = false,
+                                                     uint32_t* n_equal = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63;
     uint32_t* histA = sh.hist;
     uint32_t* histB = sh.hist + kBinsA;
@@ -156,28 +157,55 @@ __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS
         __syncthreads();
     }
 
+    // Many equal keys ("tie storms": an all-zero vector, the high digits of stamps) would
+    // serialise their LDS adds on one address.  Per key, merging equal digits costs more
+    // instructions than the add itself, and this kernel is bound by instruction issue; so
+    // the plain add is the default and the merged forms are chosen per wavefront (digit 1:
+    // all of its keys share the digit) or per pass (digits 2, 3: the bin being refined holds
+    // more than kStorm keys).
+    constexpr uint32_t kStorm = 2048;
+
     // digit 1: bits 31..20, every key
+    if (SKIP_ZERO) {
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) hist_add<SKIP_ZERO>(histA, key[j] >> 20, key[j], lane);
+        for (int j = 0; j < ITEMS; ++j) hist_add<true>(histA, key[j] >> 20, key[j], lane);
+    } else {
+        const uint32_t k0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)key[0]);
+        uint32_t diff = 0u;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) diff |= key[j] ^ k0;
+        if (__ballot((diff >> 20) != 0u) == 0ull) {      // wave-uniform branch
+            if (lane == 0) atomicAdd(&histA[k0 >> 20], 64u * ITEMS);
+        } else {
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) atomicAdd(&histA[key[j] >> 20], 1u);
+        }
+    }
     __syncthreads();
     uint32_t b1, above, inbin;
     find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
     uint32_t remaining = k - above;
 
     // digit 2: bits 19..10, only the keys of the threshold bin (a few per cent of the vector)
+    if (inbin > kStorm || SKIP_ZERO) {
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
-        if ((key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u)) {
-            // merge the lanes of a wavefront that share the digit of its first caller
-            const uint32_t d = (key[j] >> 10) & 1023u;
-            const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-            const uint64_t same = __ballot(d == d0);
-            if (d == d0) {
-                if (lanes_below(same) == 0u) atomicAdd(&histB[d0], (uint32_t)__popcll(same));
-            } else {
-                atomicAdd(&histB[d], 1u);
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 20) == b1 && (!SKIP_ZERO || key[j] != 0u)) {
+                // merge the lanes of a wavefront that share the digit of its first caller
+                const uint32_t d = (key[j] >> 10) & 1023u;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d == d0) {
+                    if (lanes_below(same) == 0u) atomicAdd(&histB[d0], (uint32_t)__popcll(same));
+                } else {
+                    atomicAdd(&histB[d], 1u);
+                }
             }
-        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 20) == b1) atomicAdd(&histB[(key[j] >> 10) & 1023u], 1u);
+    }
     __syncthreads();
     uint32_t b2;
     find_bin<1>(histB, remaining, sh, phase, b2, above, inbin);
@@ -185,23 +213,30 @@ __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS
     const uint32_t hi = (b1 << 10) | b2;
 
     // digit 3: bits 9..0
+    if (inbin > kStorm || SKIP_ZERO) {
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
-        if ((key[j] >> 10) == hi && (!SKIP_ZERO || key[j] != 0u)) {
-            const uint32_t d = key[j] & 1023u;
-            const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-            const uint64_t same = __ballot(d == d0);
-            if (d == d0) {
-                if (lanes_below(same) == 0u) atomicAdd(&histC[d0], (uint32_t)__popcll(same));
-            } else {
-                atomicAdd(&histC[d], 1u);
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 10) == hi && (!SKIP_ZERO || key[j] != 0u)) {
+                const uint32_t d = key[j] & 1023u;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d == d0) {
+                    if (lanes_below(same) == 0u) atomicAdd(&histC[d0], (uint32_t)__popcll(same));
+                } else {
+                    atomicAdd(&histC[d], 1u);
+                }
             }
-        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if ((key[j] >> 10) == hi) atomicAdd(&histC[key[j] & 1023u], 1u);
+    }
     __syncthreads();
     uint32_t b3;
     find_bin<1>(histC, remaining, sh, phase, b3, above, inbin);
     T = (hi << 10) | b3;
     need = remaining - above;
+    if (n_equal) *n_equal = inbin;   // the last digit's bin is one key value
 }
 
 // One count into hist[d] from inside divergent code: when all calling lanes of the
@@ -268,8 +303,11 @@ __device__ __forceinline__ void list_select_largest(const uint32_t* keys, uint32
 template <int LANE>
 __device__ __forceinline__ void write_lane(int& dst, uint32_t val) {
 #if SEL_WRITELANE
+    // The scalar source may have just been written by a vector instruction (a ballot): this
+    // chip wants two wait states between that write and a vector instruction reading the
+    // register, which the compiler inserts for its own code but not inside an asm statement.
     const int sval = __builtin_amdgcn_readfirstlane((int)val);
-    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(sval), "n"(LANE));
+    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(sval), "n"(LANE));
 #else
     if ((threadIdx.x & 63) == LANE) dst = (int)val;
 #endif
@@ -282,6 +320,10 @@ struct TileCount {
         const uint32_t cg = (uint32_t)__popcll(__ballot(key[J] > T));
         write_lane<J>(mine, ce | (cg << 16));
         if constexpr (J + 1 < ITEMS) TileCount<J + 1, ITEMS>::eq_gt(key, T, mine);
+    }
+    __device__ static __forceinline__ void ge(const uint32_t (&key)[ITEMS], uint32_t T, int& mine) {
+        write_lane<J>(mine, (uint32_t)__popcll(__ballot(key[J] >= T)));
+        if constexpr (J + 1 < ITEMS) TileCount<J + 1, ITEMS>::ge(key, T, mine);
     }
     __device__ static __forceinline__ void flag(uint32_t flags, int& mine) {
         write_lane<J>(mine, (uint32_t)__popcll(__ballot((flags >> J) & 1u)));
@@ -300,6 +342,23 @@ __device__ __forceinline__ uint32_t tile_prefix_eq_gt(const uint32_t (&key)[ITEM
     int mine = 0;
     TileCount<0, ITEMS>::eq_gt(key, T, mine);
     static_assert(ITEMS <= 64, "one lane per slot");
+    if (lane < ITEMS) sh.tile[0][lane * kWaves + wave] = (uint32_t)mine;
+    __syncthreads();
+    const uint32_t t = tid < ntiles ? sh.tile[0][tid] : 0u;
+    const uint32_t ex = block_excl_scan(t, sh, phase);
+    if (tid < ntiles) sh.tile[0][tid] = ex;
+    __syncthreads();
+    return lane < ITEMS ? sh.tile[0][lane * kWaves + wave] : 0u;
+}
+
+// Same for the single count of keys >= T per tile.
+template <int ITEMS>
+__device__ __forceinline__ uint32_t tile_prefix_ge(const uint32_t (&key)[ITEMS], uint32_t T,
+                                                   SelShared& sh, int& phase) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ntiles = ITEMS * kWaves;
+    int mine = 0;
+    TileCount<0, ITEMS>::ge(key, T, mine);
     if (lane < ITEMS) sh.tile[0][lane * kWaves + wave] = (uint32_t)mine;
     __syncthreads();
     const uint32_t t = tid < ntiles ? sh.tile[0][tid] : 0u;
@@ -332,14 +391,43 @@ __device__ __forceinline__ void store_ballot_words(uint32_t* words, int nwords, 
     if (lane == 32 && first_word + 1 < nwords) words[first_word + 1] = (uint32_t)(b >> 32);
 }
 
+// One slot of the selection `key >= T`: ballot, place in the index list, mask words.
+// (A template recursion rather than a loop: the lane numbers must be constants.)
+template <int J, int ITEMS, bool EMIT>
+struct SelectGe {
+    __device__ static __forceinline__ void run(const uint32_t (&key)[ITEMS], const float (&v)[ITEMS],
+                                               uint32_t T, int pre, int32_t* idx_out, float* val_out,
+                                               uint32_t k, uint32_t& sel, int& my_word) {
+        const bool mine = key[J] >= T;
+        const uint64_t bs = __ballot(mine);
+        if (EMIT) {
+            const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane(pre, J) + lanes_below(bs);
+            // pos < k always holds; the test keeps a logic slip from writing out of bounds
+            // (and the mask tells the compiler that a 32-bit offset is enough)
+            if (mine && pos < k) {
+                idx_out[pos & (DIP_MAX_N - 1)] = J * kSelThreads + (int)threadIdx.x;
+                val_out[pos & (DIP_MAX_N - 1)] = v[J];
+            }
+        }
+        sel |= mine ? (1u << J) : 0u;
+        write_lane<(2 * J) & 63>(my_word, (uint32_t)bs);
+        write_lane<(2 * J + 1) & 63>(my_word, (uint32_t)(bs >> 32));
+        if constexpr (J + 1 < ITEMS) SelectGe<J + 1, ITEMS, EMIT>::run(key, v, T, pre, idx_out, val_out, k, sel, my_word);
+    }
+};
+
+// A launch may carry independent pieces of work for further workgroups (blockIdx.y = 1, 2):
+// cache updates of earlier pruning points, which nothing in this token waits for, next to
+// this point's scores and top-K.
+struct SelectWork {
+    SelectParams piece[3];
+};
+
 template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, SelectParams second, SelectParams third) {
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectWork work) {
     __shared__ SelShared sh;
-    // A launch may carry independent pieces of work for further workgroups (blockIdx.y = 1, 2):
-    // cache updates of earlier pruning points, which nothing in this token waits for, next
-    // to this point's scores and top-K.
-    if (blockIdx.y == 1) p = second;
-    if (blockIdx.y == 2) p = third;
+    // (indexed in the kernel argument segment: only this workgroup's piece is loaded)
+    SelectParams p = work.piece[blockIdx.y];
     if (blockIdx.y > 0 && blockIdx.x > 0) return;   // the extra work is never a batch of rows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwords = (p.n + 31) >> 5;
@@ -354,15 +442,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
     // lowest-index tie rule never picks them while k <= n, and they need no masking.
     float v[ITEMS];
     uint32_t key[ITEMS];
-    uint32_t valid = 0, cres = 0, sel = 0;
+    uint32_t cres = 0, sel = 0;
+    // this lane's features tid, tid + 1024, ... below n: the low `mine_n` slots
+    const int mine_n = p.n > tid ? (p.n - tid - 1) / kSelThreads + 1 : 0;
+    const uint32_t valid = mine_n >= 32 ? 0xffffffffu : (1u << mine_n) - 1u;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
-        const int i = j * kSelThreads + tid;
         v[j] = 0.f;
         key[j] = 0u;
-        if (i < p.n) {
-            valid |= 1u << j;
-            if (p.v) v[j] = p.v[i];
+    }
+    if (p.v) {   // loads without branches: past the end the last element is read and dropped
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint32_t i = (uint32_t)(j * kSelThreads + tid);
+            const float t = p.v[min(i, (uint32_t)p.n - 1u) & (DIP_MAX_N - 1)];
+            v[j] = i < (uint32_t)p.n ? t : 0.f;
         }
     }
     // the radix histograms are cleared while the loads above are on their way
@@ -376,11 +470,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
         sh.cw[tid] = (rb && tid < nwords) ? rb[tid] : 0u;
         sh.mw[tid] = (p.mask_in && tid < nwords) ? p.mask_in[tid] : 0u;
         __syncthreads();
+        if (rb) {
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int w = j * (kSelThreads / 32) + (tid >> 5);
-            if ((sh.cw[w] >> (tid & 31)) & 1u) cres |= 1u << j;
-            if ((sh.mw[w] >> (tid & 31)) & 1u) sel |= 1u << j;
+            for (int j = 0; j < ITEMS; ++j)
+                cres |= ((sh.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u) << j;
+        }
+        if (p.mask_in) {
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                sel |= ((sh.mw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u) << j;
         }
         cres &= valid;
         sel &= valid;
@@ -424,37 +522,60 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p, Sel
         // histogram bit without changing the order
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) key[j] <<= 1;
-        uint32_t T, need;
-        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need, true);
-        const int pre = (int)tile_prefix_eq_gt<ITEMS>(key, T, sh, phase);
+        uint32_t T, need, n_equal;
+        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need, true, &n_equal);
         const bool want_words = p.mask_out || p.c_bits;
         // a wave ballot over slot j is two words of the mask: lane 2j keeps the low word and
         // lane 2j+1 the high word, stored to LDS once after the loop
-        uint32_t my_word = 0u;
+        int my_word = 0;
+        if (need == n_equal) {
+            // No tie is split at the threshold (the usual case): the selection is key >= T and
+            // a selected key's place in the list is the number of such keys before it.
+            const int pre = (int)tile_prefix_ge<ITEMS>(key, T, sh, phase);
+            const bool emit = p.idx_out && p.val_out;
+            // (T is made opaque here: keeping the comparison masks of the counting pass in
+            //  scalar registers for reuse costs more than comparing again)
+            uint32_t Tv = T;
+            asm volatile("" : "+v"(Tv));
+            if (emit) SelectGe<0, ITEMS, true>::run(key, v, Tv, pre, p.idx_out, p.val_out, (uint32_t)p.k, sel, my_word);
+            else SelectGe<0, ITEMS, false>::run(key, v, Tv, pre, p.idx_out, p.val_out, (uint32_t)p.k, sel, my_word);
+            if (!emit && (p.idx_out || p.val_out)) {
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * kSelThreads + tid;
-            const uint32_t packed = (uint32_t)__builtin_amdgcn_readlane(pre, j);
-            const uint32_t eq_before = packed & 0xffffu, gt_before = packed >> 16;
-            const uint64_t be = __ballot(key[j] == T);
-            bool mine = key[j] > T;
-            if (be) {
-                // ties at the threshold: the `need` lowest indices among them are selected
-                mine = mine || (key[j] == T && eq_before + lanes_below(be) < need);
+                for (int j = 0; j < ITEMS; ++j) {
+                    const bool mine = (sel >> j) & 1u;
+                    const uint32_t pos = (uint32_t)__builtin_amdgcn_readlane(pre, j) + lanes_below(__ballot(mine));
+                    if (mine && pos < (uint32_t)p.k) {
+                        if (p.idx_out) p.idx_out[pos] = j * kSelThreads + tid;
+                        if (p.val_out) p.val_out[pos] = v[j];
+                    }
+                }
             }
-            const uint64_t bs = __ballot(mine);
-            const uint32_t pos = gt_before + min(eq_before, need) + lanes_below(bs);
-            // pos < k always holds; the test keeps a logic slip from writing out of bounds
-            if (mine && pos < (uint32_t)p.k) {
-                if (p.idx_out) p.idx_out[pos] = i;
-                if (p.val_out) p.val_out[pos] = v[j];
+        } else {
+            const int pre = (int)tile_prefix_eq_gt<ITEMS>(key, T, sh, phase);
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const int i = j * kSelThreads + tid;
+                const uint32_t packed = (uint32_t)__builtin_amdgcn_readlane(pre, j);
+                const uint32_t eq_before = packed & 0xffffu, gt_before = packed >> 16;
+                const uint64_t be = __ballot(key[j] == T);
+                bool mine = key[j] > T;
+                if (be) {
+                    // ties at the threshold: the `need` lowest indices among them are selected
+                    mine = mine || (key[j] == T && eq_before + lanes_below(be) < need);
+                }
+                const uint64_t bs = __ballot(mine);
+                const uint32_t pos = gt_before + min(eq_before, need) + lanes_below(bs);
+                if (mine && pos < (uint32_t)p.k) {
+                    if (p.idx_out) p.idx_out[pos] = i;
+                    if (p.val_out) p.val_out[pos] = v[j];
+                }
+                sel |= mine ? (1u << j) : 0u;
+                my_word = lane == 2 * j ? (int)(uint32_t)bs : my_word;
+                my_word = lane == 2 * j + 1 ? (int)(uint32_t)(bs >> 32) : my_word;
             }
-            sel |= mine ? (1u << j) : 0u;
-            my_word = lane == 2 * j ? (uint32_t)bs : my_word;
-            my_word = lane == 2 * j + 1 ? (uint32_t)(bs >> 32) : my_word;
         }
         if (want_words && lane < 2 * ITEMS)
-            sh.mw[(lane >> 1) * (kSelThreads / 32) + wave * 2 + (lane & 1)] = my_word;
+            sh.mw[(lane >> 1) * (kSelThreads / 32) + wave * 2 + (lane & 1)] = (uint32_t)my_word;
         if (want_words) __syncthreads();
         if (p.mask_out && tid < nwords) p.mask_out[tid] = sh.mw[tid];
     }
@@ -650,13 +771,15 @@ template <int ITEMS>
 hipError_t launch_items(const SelectParams& p, const SelectParams* second, const SelectParams* third,
                         hipStream_t stream, int prof_kind) {
     const dim3 grid(p.rows > 1 ? p.rows : 1, third ? 3 : (second ? 2 : 1));
-    const SelectParams& q = second ? *second : p;
-    const SelectParams& r = third ? *third : p;
+    SelectWork work;
+    work.piece[0] = p;
+    work.piece[1] = second ? *second : p;
+    work.piece[2] = third ? *third : p;
     hipEvent_t e0, e1;
     if (prof_kind >= 0 && prof_next(prof_kind, &e0, &e1)) {
-        hipExtLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, e0, e1, 0, p, q, r);
+        hipExtLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, e0, e1, 0, work);
     } else {
-        hipLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, p, q, r);
+        hipLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, work);
     }
     return hipGetLastError();
 }
