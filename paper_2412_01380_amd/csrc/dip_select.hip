@@ -632,10 +632,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectWork work) {
         const bool need_stamps = (n_evict > 0 && !evict_all) || p.policy == DIP_LFU;
         uint32_t stamp_old[ITEMS];
         if (need_stamps) {
+            // (slots past n read the last stamp; nothing below uses them: their residency and
+            //  mask bits are zero)
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) {
-                const int i = j * kSelThreads + tid;
-                stamp_old[j] = ((valid >> j) & 1u) ? p.c_stamp[i] : 0u;
+                const uint32_t i = (uint32_t)(j * kSelThreads + tid);
+                stamp_old[j] = p.c_stamp[min(i, (uint32_t)p.n - 1u) & (DIP_MAX_N - 1)];
             }
         }
         if (evict_all) {
@@ -713,16 +715,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectWork work) {
         __syncthreads();
         // stamps: LRU marks everything used by this token that is resident afterwards
         // (hits and inserted columns); LFU counts every use
+        if (p.policy == DIP_LFU) {
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * kSelThreads + tid;
-            if ((sel >> j) & 1u) {
-                if (p.policy == DIP_LFU) {
-                    p.c_stamp[i] = stamp_old[j] + 1u;
-                } else if ((sh.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u) {
-                    p.c_stamp[i] = t_now;
-                }
-            }
+            for (int j = 0; j < ITEMS; ++j)
+                if ((sel >> j) & 1u) p.c_stamp[(uint32_t)(j * kSelThreads + tid) & (DIP_MAX_N - 1)] = stamp_old[j] + 1u;
+        } else {
+            uint32_t upd = 0u;
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                upd |= ((sh.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u) << j;
+            upd &= sel;
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                if ((upd >> j) & 1u) p.c_stamp[(uint32_t)(j * kSelThreads + tid) & (DIP_MAX_N - 1)] = t_now;
         }
         if (tid == 0) {
             p.c_meta[DIP_META_STEP] = t_now + 1u;
