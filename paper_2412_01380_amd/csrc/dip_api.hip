@@ -495,19 +495,19 @@ BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
     pl.wd = (pl.d + 31) / 32; pl.wf = (pl.f + 31) / 32;
     pl.k1max = std::min(pl.d, B * k_in);
     pl.k2max = std::min(pl.f, B * k_mid);
-    pl.g1 = batched_shares(mlp->w_ug.dtype, 2 * pl.f, pl.k1max);
-    pl.g2 = batched_shares(mlp->w_d.dtype, pl.d, pl.k2max);
+    pl.g1 = batched_shares(mlp->w_ug.dtype, B, 2 * pl.f, pl.k1max);
+    pl.g2 = batched_shares(mlp->w_d.dtype, B, pl.d, pl.k2max);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     pl.off_m1 = take(sizeof(uint32_t) * B * pl.wd);
     pl.off_u1 = take(sizeof(uint32_t) * pl.wd);
-    // index and multiplier lists carry 8 spare entries: the product reads whole vectors
-    pl.off_idx1 = take(sizeof(int32_t) * (pl.k1max + 8));
-    pl.off_val1 = take(sizeof(float) * (size_t)(pl.k1max + 8) * B);
+    // index and multiplier lists carry 16 spare entries: the product reads whole vectors
+    pl.off_idx1 = take(sizeof(int32_t) * (pl.k1max + 16));
+    pl.off_val1 = take(sizeof(float) * (size_t)(pl.k1max + 16) * B);
     pl.off_m2 = take(sizeof(uint32_t) * B * pl.wf);
     pl.off_u2 = take(sizeof(uint32_t) * pl.wf);
-    pl.off_idx2 = take(sizeof(int32_t) * (pl.k2max + 8));
-    pl.off_val2 = take(sizeof(float) * (size_t)(pl.k2max + 8) * B);
+    pl.off_idx2 = take(sizeof(int32_t) * (pl.k2max + 16));
+    pl.off_val2 = take(sizeof(float) * (size_t)(pl.k2max + 16) * B);
     pl.off_cnt = take(sizeof(uint32_t) * 2);
     pl.off_h = take(sizeof(float) * (size_t)B * pl.f);
     const size_t p1 = sizeof(float) * (size_t)pl.g1 * B * 2 * pl.f;

@@ -9,9 +9,11 @@
 //
 // Kernels in this file:
 //   union_kernel     union of the B row masks -> ascending index list, its length, and the
-//                    B multipliers of every listed column (lists padded by 8 entries)
+//                    B multipliers of every listed column (lists padded by 16 entries)
 //   bgemv_kernel     column-gathered product for all B rows at once, partial sums per
 //                    row share; the number of listed columns is read from device memory
+//   bgemv_q4_mfma_kernel  the same product for int4 weights and three or more rows, as a
+//                    dense contraction on the matrix cores
 //   breduce_kernel   adds the partial sums in share order and applies the epilogue
 //                    (SwiGLU for the bundled up/gate matrix, Sec. 3 Eq. 2)
 
@@ -307,6 +309,177 @@ __global__ __launch_bounds__(kBWaves * 64) void bgemv_kernel(BatchedGemvParams p
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// int4-g128 weights, more than kMfmaMinBatch rows: the product on the matrix cores.
+//
+// With B rows the union columns times the row multipliers is a dense contraction
+//     P[b][j] = sum_u  m[b][u] * scale[u][j / 128] * q[u][j],
+// B x K_union x n_out, and on the vector ALU every 4-bit code costs B multiply-adds plus its
+// unpacking.  v_mfma_f32_16x16x16_f16 takes it instead: M = batch row (16, the rows past B are
+// zero), K = 16 listed columns, N = 16 stored columns.  The scale belongs to (u, 128-column
+// group), so it goes into the left operand next to the multiplier -- m * scale is rounded to
+// fp16 once (relative error 2^-12 per term) -- and the right operand holds the codes q + 8 in
+// [0, 15], exact in fp16.  Sums are fp32; the offset leaves as  -8 * sum_u m*scale, which a
+// product with an all-ones right operand supplies.
+//
+// Lane l of a wavefront: k-block r = l / 16 (listed columns 4r .. 4r+3 of the 16), c = l % 16.
+// Right operand: the lane loads one dword = 8 codes of each of its 4 stored rows at byte 4c of
+// the group's 64-byte piece; product number t (0..7) takes code t of the four dwords, so it
+// yields the stored columns 8c + t.  Left operand: the lane is batch row c; it multiplies that
+// row's multiplier of its 4 listed columns by the scale of (column, group).
+// A workgroup covers two groups (256 stored columns, one 128-byte piece per row) and a share
+// of the listed columns; its wavefronts take sets of 16 listed columns in turn.
+// ---------------------------------------------------------------------------------------
+typedef _Float16 h4_t __attribute__((ext_vector_type(4)));
+typedef float f4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaMinBatch = 3;
+constexpr int kMWaves = 4;
+constexpr int kMGroups = 2;
+constexpr int kMStripCols = 128 * kMGroups;
+constexpr int kMRowSet = 16;
+
+__device__ __forceinline__ h4_t pack_h4(float a, float b, float c, float d) {
+    // round-toward-zero packing is exact here: the values are integers in [0, 15]
+    struct { decltype(__builtin_amdgcn_cvt_pkrtz(0.f, 0.f)) lo, hi; } v = {__builtin_amdgcn_cvt_pkrtz(a, b),
+                                                                         __builtin_amdgcn_cvt_pkrtz(c, d)};
+    return __builtin_bit_cast(h4_t, v);
+}
+
+__global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemvParams p) {
+    __shared__ float red[kMGroups][8][8][16];    // [group][code position][batch row][lane column]
+    __shared__ float red1[kMGroups][8];          // sum of m*scale per (group, batch row)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane >> 4, c = lane & 15;
+    const int strip = blockIdx.x, g = blockIdx.y, G = gridDim.y;
+    const int B = p.batch;
+    const int ngroups = p.n_out >> 7;
+
+    const int k = min((int)p.k_dev[0], p.k_max);
+    const int share = ((k + G - 1) / G + kMRowSet - 1) / kMRowSet * kMRowSet;
+    const int kb = min(k, g * share), ke = min(k, kb + share);
+
+    f4_t acc[kMGroups][8], acc1[kMGroups];
+#pragma unroll
+    for (int gg = 0; gg < kMGroups; ++gg) {
+        acc1[gg] = f4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[gg][t] = f4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    // a ragged last strip has one group only: the second is re-read from the first and dropped
+    int grp[kMGroups];
+#pragma unroll
+    for (int gg = 0; gg < kMGroups; ++gg) grp[gg] = min(strip * kMGroups + gg, ngroups - 1);
+    const h4_t ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
+    const bool row_live = c < B;
+
+    // One set of 16 listed columns per step; the index vector of the next set is requested
+    // before the current one is multiplied.  Nothing branches on a lane: positions past the
+    // share read stored row 0 and are masked out of the left operand.  Offsets are 32-bit
+    // (a stored matrix is far below 4 GB) on top of scalar base pointers.
+    constexpr int STEP = kMWaves * kMRowSet;
+    // (the lists carry 16 spare entries past k_max, so whole index vectors may be read there)
+    auto load_idx = [&](int t) {
+        return *reinterpret_cast<const int4*>(p.uidx + min(t, p.k_max) + 4 * r);
+    };
+    const char* wbytes = static_cast<const char*>(p.w);
+    const uint32_t row_stride = (uint32_t)p.row_stride;
+    const uint32_t wcol[kMGroups] = {(uint32_t)(grp[0] * 64 + 4 * c), (uint32_t)(grp[1] * 64 + 4 * c)};
+    const uint32_t cb = (uint32_t)min(c, B - 1);
+    int4 rn = load_idx(kb + wave * kMRowSet);
+    for (int t0 = kb + wave * kMRowSet; t0 < ke; t0 += STEP) {
+        const int rows[4] = {rn.x, rn.y, rn.z, rn.w};
+        rn = load_idx(t0 + STEP);
+        uint32_t wq[kMGroups][4];
+        uint16_t sc[kMGroups][4];
+        float mv[4];
+        uint32_t keep[2] = {0u, 0u};    // bit masks over the two fp16 pairs of the left operand
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = t0 + 4 * r + i;
+            const bool live = u < ke && (unsigned)rows[i] < (unsigned)p.n_in;
+            const uint32_t rr = live ? (uint32_t)rows[i] : 0u;
+            // entries past the share hold whatever the list memory held: they are masked out
+            // of the left operand bit-wise (never multiplied away), and the mask is plain
+            // arithmetic so that the load stays unconditional
+            mv[i] = p.uval[(uint32_t)min(u, p.k_max - 1) * (uint32_t)B + cb];
+            if (live && row_live) keep[i >> 1] |= (i & 1) ? 0xffff0000u : 0x0000ffffu;
+            const uint32_t wrow = rr * row_stride;
+            const uint32_t srow = rr * (uint32_t)p.scale_stride;
+#pragma unroll
+            for (int gg = 0; gg < kMGroups; ++gg) {
+                wq[gg][i] = *reinterpret_cast<const uint32_t*>(wbytes + (wrow + wcol[gg]));
+                sc[gg][i] = p.scales[srow + (uint32_t)grp[gg]];
+            }
+        }
+#pragma unroll
+        for (int gg = 0; gg < kMGroups; ++gg) {
+            float ms[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                _Float16 hs;
+                __builtin_memcpy(&hs, &sc[gg][i], 2);
+                ms[i] = mv[i] * (float)hs;
+            }
+            const h4_t a_all = {(_Float16)ms[0], (_Float16)ms[1], (_Float16)ms[2], (_Float16)ms[3]};
+            struct { uint32_t lo, hi; } ab = __builtin_bit_cast(decltype(ab), a_all);
+            ab.lo &= keep[0];
+            ab.hi &= keep[1];
+            const h4_t a = __builtin_bit_cast(h4_t, ab);
+            uint32_t ev[4], od[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t o = wq[gg][i] ^ 0x88888888u;     // q -> q + 8
+                ev[i] = o & 0x0f0f0f0fu;
+                od[i] = (o >> 4) & 0x0f0f0f0fu;
+                // keeps the byte extracts below from being narrowed into bit-field extracts
+                asm volatile("" : "+v"(ev[i]), "+v"(od[i]));
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int sh = 8 * (t >> 1);
+                float f[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) f[i] = (float)((((t & 1) ? od[i] : ev[i]) >> sh) & 0xffu);
+                acc[gg][t] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pack_h4(f[0], f[1], f[2], f[3]), acc[gg][t], 0, 0, 0);
+            }
+            acc1[gg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, acc1[gg], 0, 0, 0);
+        }
+    }
+    // A result register i of lane l is batch row 4 * (l / 16) + i, lane column l % 16: the
+    // first 32 lanes hold the 8 real rows.  One wavefront after the other adds its sums into
+    // the same LDS tile (fixed order).
+    for (int w = 0; w < kMWaves; ++w) {
+        if (wave == w && lane < 32) {
+#pragma unroll
+            for (int gg = 0; gg < kMGroups; ++gg) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int b = 4 * r + i;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        float* dst = &red[gg][t][b][c];
+                        *dst = w == 0 ? acc[gg][t][i] : *dst + acc[gg][t][i];
+                    }
+                    if (c == 0) {
+                        float* dst = &red1[gg][b];
+                        *dst = w == 0 ? acc1[gg][i] : *dst + acc1[gg][i];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    for (int o = tid; o < B * kMStripCols; o += kMWaves * 64) {
+        const int b = o / kMStripCols, cc = o % kMStripCols;
+        const int gcol = strip * kMStripCols + cc;
+        if (gcol >= p.n_out) continue;
+        const int gg = cc >> 7, cl = (cc & 127) >> 3, t = cc & 7;
+        p.partial[((size_t)g * B + b) * (size_t)p.n_out + gcol] = fmaf(-8.0f, red1[gg][b], red[gg][t][b][cl]);
+    }
+}
+
 // out[b][j] = sum over shares of partial[g][b][j]   (glu == 0), or
 // out[b][j] = up * SiLU(gate), up = sum partial[g][b][j], gate = sum partial[g][b][half + j];
 // eight partial sums in flight at a time, added in share order
@@ -351,15 +524,25 @@ hipError_t launch_dt(const BatchedGemvParams& p, dim3 grid, hipStream_t stream, 
 
 }  // namespace
 
-int batched_strip_cols(int dtype) {
+bool batched_on_matrix_cores(int dtype, int batch) {
+    return dtype == DIP_INT4_G128 && batch >= kMfmaMinBatch;
+}
+
+int batched_strip_cols(int dtype, int batch) {
+    if (batched_on_matrix_cores(dtype, batch)) return kMStripCols;
     return dtype == DIP_F32 ? 16 * 4 : (dtype == DIP_BF16 ? 16 * 8 : 32 * 16);
 }
 
-int batched_shares(int dtype, int n_out, int k_max) {
-    // about 1024 workgroups, at least 32 listed columns each
-    const int strips = (n_out + batched_strip_cols(dtype) - 1) / batched_strip_cols(dtype);
-    int g = (1024 + strips - 1) / strips;
-    while (g > 1 && k_max / g < 32) --g;
+int batched_shares(int dtype, int batch, int n_out, int k_max) {
+    // Vector-ALU product: about 1024 workgroups, at least 32 listed columns each.
+    // Matrix-core product: one round of workgroups -- three of them fit a compute unit, 768
+    // in all; 840 take as long as 1536 -- and at least one set of 16 per wavefront.
+    const int sc = batched_strip_cols(dtype, batch);
+    const int strips = (n_out + sc - 1) / sc;
+    const bool mc = batched_on_matrix_cores(dtype, batch);
+    const int min_rows = mc ? kMWaves * kMRowSet : 32;
+    int g = mc ? 768 / strips : (1024 + strips - 1) / strips;
+    while (g > 1 && k_max / g < min_rows) --g;
     return g < 1 ? 1 : g;
 }
 
@@ -371,8 +554,10 @@ hipError_t launch_union(const UnionParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int pk) {
-    const int sc = batched_strip_cols(p.dtype);
+    const int sc = batched_strip_cols(p.dtype, p.batch);
     dim3 grid((p.n_out + sc - 1) / sc, shares);
+    if (batched_on_matrix_cores(p.dtype, p.batch))
+        return launch_timed(bgemv_q4_mfma_kernel, grid, dim3(kMWaves * 64), stream, pk, p);
     if (p.dtype == DIP_F32) return launch_dt<DIP_F32>(p, grid, stream, pk);
     if (p.dtype == DIP_BF16) return launch_dt<DIP_BF16>(p, grid, stream, pk);
     if (p.dtype == DIP_INT4_G128) return launch_dt<DIP_INT4_G128>(p, grid, stream, pk);

@@ -175,8 +175,9 @@ struct BatchedReduceParams {
     float* out;
     int64_t out_stride;
 };
-int batched_strip_cols(int dtype);
-int batched_shares(int dtype, int n_out, int k_max);
+bool batched_on_matrix_cores(int dtype, int batch);
+int batched_strip_cols(int dtype, int batch);
+int batched_shares(int dtype, int batch, int n_out, int k_max);
 hipError_t launch_union(const UnionParams& p, hipStream_t stream);
 hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int prof_kind);
 hipError_t launch_batched_reduce(const BatchedReduceParams& p, hipStream_t stream);
