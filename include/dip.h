@@ -19,7 +19,9 @@
  *   - All work is enqueued on the caller's stream (a hipStream_t passed as void*, NULL =
  *     the default stream).  No call synchronises with the host or reads device memory
  *     back.  Calls on one stream are ordered; calls that share a workspace or a cache on
- *     different streams race.
+ *     different streams race.  The scoring, selection, cache-update, product and forward
+ *     calls enqueue kernel launches only (no allocation, no memset, no copy), so they may
+ *     be captured into a HIP graph and replayed; dip_profile_enable must be off then.
  *   - Arguments are validated on the host before any HIP call.  On an error nothing is
  *     enqueued and no state changes.  Every function returns a dip_status; the message
  *     of the last failure on the calling thread is available from dip_last_error().
@@ -291,6 +293,9 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
  *   mask_in_out   [batch][ceil(d_model/32)] words     h_out  [batch][d_ff] floats
  *   mask_mid_out  [batch][ceil(d_ff/32)] words
  * Summation order is fixed by the launch configuration (bit-repeatable).
+ * DIP_INT4_G128 weights with batch >= 3 are multiplied on the matrix cores: activation times
+ * group scale enters as two fp16 terms (22 significant bits) and must stay below the fp16
+ * range, |x * scale| < 65504; the sums are fp32 as everywhere else.
  */
 size_t dip_swiglu_mlp_forward_batched_workspace_bytes(const dip_mlp* mlp, int32_t batch,
                                                       int32_t k_in, int32_t k_mid);

@@ -317,10 +317,11 @@ __global__ __launch_bounds__(kBWaves * 64) void bgemv_kernel(BatchedGemvParams p
 // B x K_union x n_out, and on the vector ALU every 4-bit code costs B multiply-adds plus its
 // unpacking.  v_mfma_f32_16x16x16_f16 takes it instead: M = batch row (16, the rows past B are
 // zero), K = 16 listed columns, N = 16 stored columns.  The scale belongs to (u, 128-column
-// group), so it goes into the left operand next to the multiplier -- m * scale is rounded to
-// fp16 once (relative error 2^-12 per term) -- and the right operand holds the codes q + 8 in
-// [0, 15], exact in fp16.  Sums are fp32; the offset leaves as  -8 * sum_u m*scale, which a
-// product with an all-ones right operand supplies.
+// group), so it goes into the left operand next to the multiplier: m * scale enters as the
+// sum of two fp16 numbers (its rounded value and the rounded rest, 22 significant bits; each
+// tile is multiplied twice), which requires |m * scale| < 65504, the fp16 range.  The right
+// operand holds the codes q + 8 in [0, 15], exact in fp16.  Sums are fp32; the offset leaves
+// as  -8 * sum_u m*scale, which a product with an all-ones right operand supplies.
 //
 // Lane l of a wavefront: k-block r = l / 16 (listed columns 4r .. 4r+3 of the 16), c = l % 16.
 // Right operand: the lane loads one dword = 8 codes of each of its 4 stored rows at byte 4c of
@@ -422,11 +423,20 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
                 __builtin_memcpy(&hs, &sc[gg][i], 2);
                 ms[i] = mv[i] * (float)hs;
             }
-            const h4_t a_all = {(_Float16)ms[0], (_Float16)ms[1], (_Float16)ms[2], (_Float16)ms[3]};
-            struct { uint32_t lo, hi; } ab = __builtin_bit_cast(decltype(ab), a_all);
-            ab.lo &= keep[0];
-            ab.hi &= keep[1];
-            const h4_t a = __builtin_bit_cast(h4_t, ab);
+            // m * scale as a sum of two fp16 numbers: the rounded value and the rounded rest
+            // (a denormal, which the matrix cores keep): 22 significant bits instead of 11
+            _Float16 top[4], rest[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                top[i] = (_Float16)ms[i];
+                rest[i] = (_Float16)(ms[i] - (float)top[i]);
+            }
+            struct Pair { uint32_t lo, hi; };
+            Pair pa = __builtin_bit_cast(Pair, h4_t{top[0], top[1], top[2], top[3]});
+            Pair pb = __builtin_bit_cast(Pair, h4_t{rest[0], rest[1], rest[2], rest[3]});
+            pa.lo &= keep[0]; pa.hi &= keep[1];
+            pb.lo &= keep[0]; pb.hi &= keep[1];
+            const h4_t a = __builtin_bit_cast(h4_t, pa), a2 = __builtin_bit_cast(h4_t, pb);
             uint32_t ev[4], od[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -442,9 +452,12 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
                 float f[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) f[i] = (float)((((t & 1) ? od[i] : ev[i]) >> sh) & 0xffu);
-                acc[gg][t] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, pack_h4(f[0], f[1], f[2], f[3]), acc[gg][t], 0, 0, 0);
+                const h4_t codes = pack_h4(f[0], f[1], f[2], f[3]);
+                acc[gg][t] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, codes, acc[gg][t], 0, 0, 0);
+                acc[gg][t] = __builtin_amdgcn_mfma_f32_16x16x16f16(a2, codes, acc[gg][t], 0, 0, 0);
             }
             acc1[gg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, acc1[gg], 0, 0, 0);
+            acc1[gg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a2, ones, acc1[gg], 0, 0, 0);
         }
     }
     // A result register i of lane l is batch row 4 * (l / 16) + i, lane column l % 16: the
