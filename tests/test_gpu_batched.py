@@ -101,3 +101,33 @@ def test_config5_phi3_medium_int4_batched(D, B):
     cfg = CONFIGS[5]
     run_steps(D, cfg.d_model, cfg.d_ff, "int4", B, cfg.k_in(0.3), cfg.k_mid(0.3), steps=2,
               use_cache=True, seed=cfg.seed, layer=1)
+
+
+@pytest.mark.parametrize("B", [3, 5, 8])
+def test_batched_int4_matrix_core_edges(D, B):
+    """int4 with three or more rows runs on the matrix cores: an odd number of 128-column
+    scale groups (the last 256-column strip is half empty), shares shorter than one set of
+    16 listed columns, and every keep count down to 1."""
+    run_steps(D, 640, 1408, "int4", B, 211, 433, steps=2, use_cache=True, seed=34)
+    run_steps(D, 640, 1408, "int4", B, 17, 33, steps=2, use_cache=False, seed=35)
+    run_steps(D, 128, 128, "int4", B, 1, 1, steps=2, use_cache=True, seed=36)
+    run_steps(D, 384, 1152, "int4", B, 384, 1152, steps=1, use_cache=False, seed=37)
+
+
+def test_batched_int4_matrix_core_accuracy(D):
+    """The two-term fp16 left operand keeps the quantised product far inside the 2e-3 bar."""
+    d, f, B, k_in, k_mid = 1024, 2816, 8, 307, 845
+    w = layer_weights(d, f, seed=38, layer=0, dtype="int4")
+    mlp = D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"]))
+    ws = workspace(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlp, B, k_in, k_mid))
+    H = torch.empty(B, f, dtype=torch.float32, device="cuda")
+    Y = torch.empty(B, d, dtype=torch.float32, device="cuda")
+    X = np.stack([ar1_laplace_stream(1, d, seed=380 + b)[0] for b in range(B)])
+    D.dip_swiglu_mlp_forward_batched(mlp, dev_f32(X), B, k_in, k_mid, None, None, 0.2, Y, None, H, None, ws)
+    torch.cuda.synchronize()
+    Hg, Yg = H.cpu().numpy(), Y.cpu().numpy()
+    for b in range(B):
+        _, idx1 = O.topk(O.score(X[b], None, 0.2), k_in)
+        assert rel_l2(Hg[b], O.glu_from_preacts(O.gathered_gemv(w["ug"], X[b], idx1))) <= 2e-4
+        _, idx2 = O.topk(O.score(Hg[b], None, 0.2), k_mid)
+        assert rel_l2(Yg[b], O.gathered_gemv(w["d"], Hg[b], idx2)) <= 2e-4
