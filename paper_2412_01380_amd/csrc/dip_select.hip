@@ -15,6 +15,13 @@
 // into the threshold bin (a few per cent of the vector).  Eviction victims (smallest
 // (stamp, index) first) are the largest ages (current step - stamp) among the evictable
 // columns, found by the same radix select.
+//
+// The kernel is bound by instruction issue on its one compute unit (16 wavefronts share 4
+// SIMDs: every instruction executed per key costs 16 cycles of the workgroup), not by LDS
+// atomics or memory, so each stage is written for the fewest instructions per key: plain
+// histogram adds with the tie-storm handling hoisted out of the per-key path, branch-free
+// clamped loads, one compare per key on the usual path where no tie is split at the
+// threshold.
 #include "dip_internal.h"
 
 #ifndef SEL_WRITELANE
@@ -83,22 +90,10 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// One count per lane into hist[d]; all 64 lanes of the wavefront must call.  When they all
-// carry the same digit -- tie storms, the high digits of stamps -- lane 0 adds 64 at once
-// instead of 64 serialised LDS atomics.  SKIP_ZERO leaves out lanes whose key is 0 (used
-// where most lanes hold a non-participating column).
-template <bool SKIP_ZERO>
-__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t d, uint32_t key, int lane) {
-    if (SKIP_ZERO) {
-        if (key != 0u) atomicAdd(&hist[d], 1u);
-    } else {
-        const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-        if (__ballot(d != d0) == 0ull) {      // wave-uniform branch
-            if (lane == 0) atomicAdd(&hist[d0], 64u);
-        } else {
-            atomicAdd(&hist[d], 1u);
-        }
-    }
+// One count into hist[d] for every lane whose key is not 0 (eviction keys: most lanes hold a
+// column that does not take part).
+__device__ __forceinline__ void hist_add_nonzero(uint32_t* hist, uint32_t d, uint32_t key) {
+    if (key != 0u) atomicAdd(&hist[d], 1u);
 }
 
 // Scan the bins from the top: find the bin in which the running count reaches `want`.
@@ -168,7 +163,7 @@ __device__ __forceinline__ void block_select_largest(const uint32_t (&key)[ITEMS
     // digit 1: bits 31..20, every key
     if (SKIP_ZERO) {
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) hist_add<true>(histA, key[j] >> 20, key[j], lane);
+        for (int j = 0; j < ITEMS; ++j) hist_add_nonzero(histA, key[j] >> 20, key[j]);
     } else {
         const uint32_t k0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)key[0]);
         uint32_t diff = 0u;
