@@ -674,6 +674,9 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
                 ks = whole_rounds(lprs[li], 200, 400);
                 if (ks) s.lpr = lprs[li];
             }
+        } else {
+            // single matrix (down): whole rounds when the shares come out at 420-700 rows
+            ks = whole_rounds(16, 420, 700);
         }
     }
     // a bundled strip needs 2*SC lanes for its epilogue
