@@ -269,6 +269,24 @@ int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in,
                                size_t ws_bytes, void* stream);
 
 /*
+ * dip_swiglu_mlp_forward for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and ordering rules as dip_swiglu_mlp_forward, minus
+ * the workspace: the scratch (index lists, h~, split-K partial sums, ticket counters) lives
+ * in a device array built into the library, DIP_STATIC_SCRATCH_BYTES per GPU, held from
+ * library load until the process ends.  The call allocates and frees nothing.  A layer
+ * whose dip_swiglu_mlp_forward_workspace_bytes() exceeds DIP_STATIC_SCRATCH_BYTES is
+ * rejected with DIP_ERR_WORKSPACE and nothing is enqueued.  All calls on one GPU share that
+ * GPU's array (it keeps the previous call's contents; what must start at zero is cleared by
+ * the call's own kernels): calls that overlap on one GPU -- different streams, or replays
+ * of graphs that contain it running concurrently -- race.
+ */
+#define DIP_STATIC_SCRATCH_BYTES (4u << 20)
+int32_t dip_swiglu_mlp_forward_noalloc(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                                       const dip_cache* cache_in, const dip_cache* cache_mid,
+                                       float gamma, float* y_out, const dip_debug* dbg, void* stream);
+
+/*
  * The same forward for n_layers independent layers in one call (a decode step over a
  * stack): layer l reads x + l * x_stride and writes y_out + l * y_stride (strides in
  * floats).  mlps / caches_in / caches_mid are host arrays of n_layers descriptors; the

@@ -10,7 +10,8 @@ from .libdip import (  # noqa: F401
     DipError, Cache, Debug, Mlp, Weight, lib, lib_path,
     dip_ca_scores, dip_cache_init, dip_cache_update, dip_gathered_gemv,
     dip_gathered_gemv_workspace_bytes, dip_last_error, dip_prune_topk,
-    dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack,
+    dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack, dip_swiglu_mlp_forward_noalloc,
+    DIP_STATIC_SCRATCH_BYTES,
     dip_swiglu_mlp_forward_workspace_bytes, dip_tune_gemv, dip_version, MlpStack, EXPORTS, META,
     dip_gemv_launch_shape, dip_profile_enable,
     dip_cache_state_bytes, dip_cache_blob_bytes, dip_cache_export, dip_cache_import,

@@ -2,6 +2,7 @@
 // stream.  Nothing here allocates device memory, synchronises, or reads device data.
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -471,6 +472,52 @@ int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in,
                                void* stream) {
     return forward_checked(mlp, 1, x, 0, k_in, k_mid, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
                            ws_bytes, stream);
+}
+
+// ---- the forward for callers that cannot allocate ------------------------------------------
+// The workspace of dip_swiglu_mlp_forward, held in the library's own device memory: one
+// array per GPU, present from the moment the code object is loaded until the process ends.
+// In host code `g_static_scratch` is only a handle for hipGetSymbolAddress; the address the
+// kernels get is the one that call returns for the current device.
+static __device__ __align__(256) unsigned char g_static_scratch[DIP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int32_t static_scratch(void** out) {
+    int dev = -1;
+    int32_t st = check_hip(hipGetDevice(&dev), "hipGetDevice");
+    if (st) return st;
+    if (dev < 0 || dev >= kMaxDevices) return fail(DIP_ERR_UNSUPPORTED, "device ordinal %d not supported", dev);
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // every thread that gets here asks for the same address of the same device
+        st = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)), "hipGetSymbolAddress");
+        if (st) return st;
+        if (!p) return fail(DIP_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return DIP_OK;
+}
+}  // namespace
+
+int32_t dip_swiglu_mlp_forward_noalloc(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
+                                       const dip_cache* cache_in, const dip_cache* cache_mid,
+                                       float gamma, float* y_out, const dip_debug* dbg, void* stream) {
+    int32_t st = validate_mlp(mlp, k_in, k_mid);
+    if (st) return st;
+    const size_t need = plan_forward(mlp, k_in, k_mid).total;
+    if (need > (size_t)DIP_STATIC_SCRATCH_BYTES)
+        return fail(DIP_ERR_WORKSPACE,
+                    "dip_swiglu_mlp_forward_noalloc: this layer needs %zu bytes of scratch, the built-in "
+                    "buffer holds %zu; use dip_swiglu_mlp_forward with a caller workspace",
+                    need, (size_t)DIP_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if ((st = static_scratch(&ws))) return st;
+    return forward_checked(mlp, 1, x, 0, k_in, k_mid, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
+                           (size_t)DIP_STATIC_SCRATCH_BYTES, stream);
 }
 
 int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,

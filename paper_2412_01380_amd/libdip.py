@@ -105,6 +105,9 @@ def _load() -> C.CDLL:
     L.dip_swiglu_mlp_forward.restype = i32
     L.dip_swiglu_mlp_forward.argtypes = [C.POINTER(_Mlp), vp, i32, i32, C.POINTER(_Cache),
                                          C.POINTER(_Cache), f32, vp, C.POINTER(_Debug), vp, sz, vp]
+    L.dip_swiglu_mlp_forward_noalloc.restype = i32
+    L.dip_swiglu_mlp_forward_noalloc.argtypes = [C.POINTER(_Mlp), vp, i32, i32, C.POINTER(_Cache),
+                                                 C.POINTER(_Cache), f32, vp, C.POINTER(_Debug), vp]
     L.dip_swiglu_mlp_forward_stack.restype = i32
     L.dip_swiglu_mlp_forward_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, i32, i32,
                                                C.POINTER(_Cache), C.POINTER(_Cache), f32, vp, i64,
@@ -153,7 +156,7 @@ EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "
            "dip_cache_update", "dip_cache_state_bytes", "dip_cache_blob_bytes", "dip_cache_export",
            "dip_cache_import", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
-           "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
+           "dip_swiglu_mlp_forward_noalloc", "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
            "dip_swiglu_mlp_forward_batched", "dip_glu_pruning_forward_workspace_bytes",
            "dip_glu_pruning_forward", "dip_gathered_rowdot",
            "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tier_init_workspace_bytes",
@@ -406,6 +409,21 @@ def dip_swiglu_mlp_forward(mlp: Mlp, x, k_in: int, k_mid: int, cache_in: Optiona
         C.byref(cache_mid.c) if cache_mid is not None else None,
         gamma, _ptr(y_out, torch.float32), C.byref(dbg.c) if dbg is not None else None,
         _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+DIP_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def dip_swiglu_mlp_forward_noalloc(mlp: Mlp, x, k_in: int, k_mid: int, cache_in: Optional[Cache],
+                                   cache_mid: Optional[Cache], gamma: float, y_out,
+                                   dbg: Optional[Debug], stream=None) -> None:
+    import torch
+    _check(lib.dip_swiglu_mlp_forward_noalloc(
+        C.byref(mlp.c), _ptr(x, torch.float32), k_in, k_mid,
+        C.byref(cache_in.c) if cache_in is not None else None,
+        C.byref(cache_mid.c) if cache_mid is not None else None,
+        gamma, _ptr(y_out, torch.float32), C.byref(dbg.c) if dbg is not None else None,
+        _stream(stream)))
 
 
 class MlpStack:
