@@ -6,7 +6,12 @@ up/gate GEMV + SwiGLU -> scores -> top-K -> gathered down GEMV, plus the cache u
 the DIP-CA configurations), called through the C ABI of libdip.  All inputs are synthetic
 and resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4] [--ratio R]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--ratio R] [--cache-frac C]
+
+The default workload is BASELINE configs[3]: the Phi-3-Medium-shaped stack of 40 bf16 layers,
+keep ratio 0.3, DIP-CA with an LRU cache over half of the columns, gamma 0.2.  Steps walk the
+stack token-major; exactly --steps of them form a timed block, and the reported time is the
+median over --repeats repeats of that block (run back to back until a repeat lasts 20 ms).
 """
 from __future__ import annotations
 
@@ -26,9 +31,21 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4096)
-    ap.add_argument("--warmup", type=int, default=256)
-    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5))
+    ap.add_argument("--steps", type=int, default=2000,
+                    help="layer-steps per timed block (one token through one MLP layer each)")
+    ap.add_argument("--warmup", type=int, default=400, help="untimed layer-steps before the first timed block")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repeats; the median is reported")
+    ap.add_argument("--min-repeat-ms", type=float, default=20.0,
+                    help="a repeat runs the block of --steps steps as many times as it takes to last this long")
+    ap.add_argument("--config", type=int, default=4, choices=(2, 3, 4, 5),
+                    help="BASELINE config number (1-based); default 4 = configs[3], the Phi-3-Medium-shaped stack")
+    ap.add_argument("--policy", default="lru", choices=("lru", "lfu"))
+    ap.add_argument("--tokens", type=int, default=512, help="distinct tokens per layer stream (then it wraps)")
+    ap.add_argument("--no-fusion", action="store_true",
+                    help="launch selection and product apart (two launches per pruning point)")
+    ap.add_argument("--no-side-runs", action="store_true",
+                    help="skip the LRU/LFU x gamma hit-rate runs and the simulated-mobile figures")
+    ap.add_argument("--side-tokens", type=int, default=48)
     ap.add_argument("--ratio", type=float, default=None, help="keep ratio at both pruning points")
     ap.add_argument("--cache-frac", type=float, default=None)
     ap.add_argument("--layers", type=int, default=None,
@@ -308,6 +325,56 @@ def bench_tiered(a):
     print(json.dumps(out))
 
 
+PAPER_TABLE2_PHI3_MEDIUM = {
+    # context only: simulated Apple-A18 (DRAM 60 GB/s, Flash 1 GB/s), INT4 GPTQ, LFU cache,
+    # model 7.4 GB with 4.0 GB of DRAM (Table 2, Phi-3-Medium column)
+    "dense": 0.29, "dip_at_+0.2ppl": 0.43, "dip_ca_at_+0.2ppl": 0.45,
+    "dip_at_+0.5ppl": 0.50, "dip_ca_at_+0.5ppl": 0.56,
+}
+
+
+def build_layers(D, cfg, L, workers=6):
+    """Weights of L layers on the device (generated on host threads: numpy releases the GIL in
+    its generators), layer 0 also kept on the host for the oracle sample."""
+    import numpy as np
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from workloads import layer_weights
+
+    d, f = cfg.d_model, cfg.d_ff
+    if cfg.dtype == "int4":
+        mk = lambda t: D.Weight(torch.from_numpy(t[0]).cuda(), torch.from_numpy(t[1]).cuda())
+    else:
+        mk = lambda arr: D.Weight(torch.from_numpy(arr.view(np.int16)).cuda())
+    mlps, host0 = [], None
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        pending = []
+        for l in range(L):
+            pending.append(pool.submit(layer_weights, d, f, cfg.seed, l, cfg.dtype))
+            # bounded look-ahead: a layer in fp32 on the host is over a gigabyte
+            while pending and (len(pending) >= workers or l == L - 1):
+                w = pending.pop(0).result()
+                if host0 is None:
+                    host0 = w
+                mlps.append(D.Mlp(mk(w["ug"]), mk(w["d"])))
+                del w
+    return mlps, host0
+
+
+def hit_rates(D, cins, cmids, before=None):
+    """Hit rates from the cache states' own counters (dip_cache.meta) through the two-tier
+    model's reader; `before` = an earlier reading to take the difference with."""
+    from paper_2412_01380_amd.twotier import hit_rates_from_meta
+    mi = [c.meta_host() for c in cins]
+    mm = [c.meta_host() for c in cmids]
+    tot = {"in": {"cum_hits": sum(m["cum_hits"] for m in mi), "cum_lookups": sum(m["cum_lookups"] for m in mi)},
+           "mid": {"cum_hits": sum(m["cum_hits"] for m in mm), "cum_lookups": sum(m["cum_lookups"] for m in mm)}}
+    if before is None:
+        return tot, hit_rates_from_meta(tot["in"], tot["mid"])
+    diff = {p: {k: tot[p][k] - before[p][k] for k in tot[p]} for p in tot}
+    return tot, hit_rates_from_meta(diff["in"], diff["mid"])
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -316,15 +383,20 @@ def main():
               "but no multi-GPU figure is produced.", file=sys.stderr)
         sys.exit(2)
 
+    import ctypes as C
+    import statistics
     import numpy as np
     import torch
 
     import paper_2412_01380_amd as D
-    from workloads import CONFIGS, layer_weights
+    from paper_2412_01380_amd import twotier
+    from workloads import CONFIGS
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if a.tune:
         D.dip_tune_gemv(*[int(v) for v in a.tune.split(",")])
+    if a.no_fusion:
+        D.dip_set_fusion(False)
     if a.scheme != "dip":
         return bench_scheme(a)
     if a.tiered:
@@ -332,169 +404,157 @@ def main():
     torch.cuda.set_device(0)
     cfg = CONFIGS[a.config]
     r = a.ratio if a.ratio is not None else {2: 0.5, 3: 0.3, 4: 0.3, 5: 0.3}[a.config]
-    frac = a.cache_frac if a.cache_frac is not None else cfg.cache_fracs[0]
+    frac = a.cache_frac if a.cache_frac is not None else {2: None, 3: 0.5, 4: 0.5, 5: 0.5}[a.config]
+    gamma = a.gamma if a.gamma is not None else cfg.gamma
+    policy = {"lru": D.DIP_LRU, "lfu": D.DIP_LFU}[a.policy]
     d, f = cfg.d_model, cfg.d_ff
     k_in, k_mid = cfg.k_in(r), cfg.k_mid(r)
     # config 2 is one layer shape: rotate over distinct weight copies so that the 256 MB
-    # last-level cache cannot serve the reads; configs 3/4 are real stacks.
+    # last-level cache cannot serve the reads; configs 3-5 are real stacks.
     L = a.layers if a.layers is not None else {2: 8}.get(a.config, cfg.n_layers)
-    n_tok = cfg.n_tokens
+    B = a.batch
+    if B > 1:
+        assert a.config == 5 and B <= 8, "--batch applies to config 5 (1..8 rows)"
+    n_tok = min(cfg.n_tokens, a.tokens)
 
     t_setup = time.perf_counter()
-    host_w = []
-    mlps = []
-    for l in range(L):
-        w = layer_weights(d, f, cfg.seed, l, cfg.dtype)
-        if l < 1:
-            host_w.append(w)          # the oracle sample uses layer 0
-        if cfg.dtype == "int4":
-            mk = lambda t: D.Weight(torch.from_numpy(t[0]).cuda(), torch.from_numpy(t[1]).cuda())
-        else:
-            mk = lambda arr: D.Weight(torch.from_numpy(arr.view(np.int16)).cuda())
-        mlps.append(D.Mlp(mk(w["ug"]), mk(w["d"])))
-        del w
+    mlps, host0 = build_layers(D, cfg, L)
     # inputs: [token][layer][d]; every layer has its own stream (layers are not chained)
     X = np.stack([cfg.tokens(layer=l, n_tokens=n_tok) for l in range(L)], axis=1)
     Xd = torch.from_numpy(X).cuda()
     Yd = torch.empty(L, d, dtype=torch.float32, device="cuda")
     use_cache = frac is not None
+    C_in = C_mid = None
+
+    def fresh_caches(pol):
+        ci = [D.Cache(d, C_in, pol) for _ in range(L)]
+        cm = [D.Cache(f, C_mid, pol) for _ in range(L)]
+        for c in ci + cm:
+            D.dip_cache_init(c)
+        return ci, cm
+
     cins = cmids = None
     if use_cache:
         C_in, C_mid = int(np.floor(frac * d + 0.5)), int(np.floor(frac * f + 0.5))
-        cins = [D.Cache(d, C_in) for _ in range(L)]
-        cmids = [D.Cache(f, C_mid) for _ in range(L)]
-        for c in cins + cmids:
-            D.dip_cache_init(c)
-    stack = D.MlpStack(mlps, cins, cmids)
-    ws = torch.empty(D.dip_swiglu_mlp_forward_workspace_bytes(mlps[0], k_in, k_mid),
-                     dtype=torch.uint8, device="cuda")
+        cins, cmids = fresh_caches(policy)
+
+    class Runner:
+        """Issues layer-steps token-major: step s is layer s % L of token s // L.  A run of n
+        steps is the tail of the current token, whole tokens, and the head of the next one,
+        each a single call of the stack entry point over that range of layers."""
+
+        def __init__(self, cins, cmids, gamma):
+            self.cins, self.cmids, self.gamma = cins, cmids, gamma
+            self.pos = 0
+            self.ranges = {}
+            full = D.MlpStack(mlps, cins, cmids)
+            self.ws = torch.empty(D.dip_swiglu_mlp_forward_stack_workspace_bytes(full, k_in, k_mid),
+                                  dtype=torch.uint8, device="cuda")
+
+        def stack(self, l0, l1):
+            if (l0, l1) not in self.ranges:
+                m = l1 - l0
+                self.ranges[(l0, l1)] = (
+                    D.MlpStack(mlps[l0:l1], self.cins[l0:l1] if self.cins else None,
+                               self.cmids[l0:l1] if self.cmids else None),
+                    (C.c_int32 * m)(*([k_in] * m)), (C.c_int32 * m)(*([k_mid] * m)))
+            return self.ranges[(l0, l1)]
+
+        def run(self, n):
+            while n > 0:
+                t, l = divmod(self.pos, L)
+                m = min(n, L - l)
+                st, ki, km = self.stack(l, l + m)
+                D.dip_swiglu_mlp_forward_stack(st, Xd[t % n_tok, l:], d, ki, km, self.gamma, Yd[l:], d, self.ws)
+                self.pos += m
+                n -= m
+
+    if B > 1:
+        return bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gamma, k_in, k_mid, t_setup)
+
+    run = Runner(cins, cmids, gamma)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
-    # one "pass" = every layer (copy) once = L steps; steps are rounded to whole passes
-    B = a.batch
-    if B > 1:
-        assert a.config == 5 and B <= 8, "--batch applies to config 5 (1..8 rows)"
-        # row b of layer l at step t is its own stream: take B consecutive tokens of the layer's stream
-        Xb = torch.stack([Xd[(torch.arange(n_tok) + 37 * b) % n_tok] for b in range(B)], dim=2).contiguous()
-        Yb = torch.empty(L, B, d, dtype=torch.float32, device="cuda")
-        ws = torch.empty(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[0], B, k_in, k_mid),
-                         dtype=torch.uint8, device="cuda")
-
-    def run_pass(t):
-        if B == 1:
-            D.dip_swiglu_mlp_forward_stack(stack, Xd[t % n_tok], d, k_in, k_mid, cfg.gamma, Yd, d, ws)
-        else:
-            for l in range(L):
-                D.dip_swiglu_mlp_forward_batched(mlps[l], Xb[t % n_tok, l], B, k_in, k_mid,
-                                                 cins[l] if use_cache else None,
-                                                 cmids[l] if use_cache else None, cfg.gamma, Yb[l],
-                                                 None, None, None, ws)
-
-    passes_w = max(1, (a.warmup + L - 1) // L)
-    passes = max(1, (a.steps + L - 1) // L)
-    steps = passes * L
-    # config 2 at batch 1 (the headline): a step is one layer-token and the L weight copies
-    # are only visited in turn, so exactly --steps steps are timed (whole passes, then one
-    # pass over the first steps % L copies) after exactly --warmup untimed ones.  The other
-    # configurations time whole tokens (L layers each).
-    exact = a.config == 2 and B == 1 and not a.graph and not use_cache
-    if exact:
-        stacks_part = {}
-
-        def run_steps(t, n):
-            for _ in range(n // L):
-                run_pass(t)
-                t += 1
-            rem = n % L
-            if rem:
-                if rem not in stacks_part:
-                    stacks_part[rem] = D.MlpStack(mlps[:rem], None, None)
-                D.dip_swiglu_mlp_forward_stack(stacks_part[rem], Xd[t % n_tok], d, k_in, k_mid, cfg.gamma,
-                                               Yd, d, ws)
-                t += 1
-            return t
-
-        steps = max(1, a.steps)
-        warm_steps = max(0, a.warmup)
-        t_next = run_steps(0, warm_steps)
-        for rem in {steps % L} - {0}:
-            stacks_part.setdefault(rem, D.MlpStack(mlps[:rem], None, None))
+    K, W = max(1, a.steps), max(0, a.warmup)
+    # prepare every layer range a block of K steps can need, so that no descriptor is built inside a timed region
+    run.run(W)
+    torch.cuda.synchronize()
+    pos0 = run.pos
+    seen = set()
+    for blk in range(L + 1):
+        s0 = (pos0 + blk * K) % L
+        if s0 in seen:
+            break
+        seen.add(s0)
+        n, l = K, s0
+        while n > 0:
+            m = min(n, L - l)
+            run.stack(l, l + m)
+            n -= m
+            l = 0
+    # pilot block (untimed for the result): how many blocks make a repeat of >= 20 ms
+    t0 = time.perf_counter()
+    run.run(K)
+    torch.cuda.synchronize()
+    pilot = time.perf_counter() - t0
+    blocks = max(1, int(np.ceil(a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
+    hr_before = hit_rates(D, cins, cmids)[0] if use_cache else None
+    times = []
+    for _ in range(max(1, a.repeats)):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run_steps(t_next, steps)
+        for _ in range(blocks):
+            run.run(K)            # exactly K layer-steps
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        launch_mode = "launches issued from the host, step by step"
-        passes = max(1, steps // L)        # (whole passes, for the per-kernel event pass below)
-        passes_w = (warm_steps + L - 1) // L + 1
-    else:
-        for t in range(passes_w):
-            run_pass(t)
-        torch.cuda.synchronize()
-        launch_mode = "launches issued from the host, step by step"
-        warm_steps = passes_w * L
-    if exact:
-        pass
-    elif not a.graph:
-        t0 = time.perf_counter()
-        for t in range(passes):
-            run_pass(passes_w + t)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-    else:
-        # The launches of a window of consecutive passes are captured once into a HIP graph
-        # (the library only launches kernels on the given stream: no allocation, no memset, no
-        # host synchronisation) and the window is replayed: same kernels, same arguments, same
-        # order.  Cache state lives in device memory and keeps evolving from replay to replay.
-        # Measured gain over host-issued launches: 1-2 % (the kernels are long enough to hide
-        # the host's launch path), hence not the default.
-        per_pass = (4 if B == 1 else 10) * L
-        G = max(g for g in range(1, passes + 1) if passes % g == 0 and (g == 1 or g * per_pass <= 8192))
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for t in range(G):
-                run_pass(passes_w + t)
-        graph.replay()                      # one untimed replay
-        torch.cuda.synchronize()
-        warm_steps += G * L
-        t0 = time.perf_counter()
-        for _ in range(passes // G):
-            graph.replay()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        launch_mode = f"HIP graph of {G} pass(es) = {G * L} steps, replayed {passes // G} times"
+        times.append(time.perf_counter() - t0)
+    wall = statistics.median(times)
+    ms_per_step = wall / (blocks * K) * 1e3
+    steps_per_s = 1e3 / ms_per_step
 
     gathered = cfg.gathered_bytes(r)
     bytes_of = (lambda e: e // 2 + (e // 128) * 2) if cfg.dtype == "int4" else (lambda e: e * 2)
     ug_bytes = bytes_of(2 * k_in * f)
     dn_bytes = bytes_of(k_mid * d)
-    tokens_per_s = (steps / wall if a.config == 2 else passes / wall) * B   # configs 3-5: L layers per token
+    fused_ug = D.dip_fused_launch_shape(mlps[0].w_ug, k_in, bundled=True)
+    fused_dn = D.dip_fused_launch_shape(mlps[0].w_d, k_mid, bundled=False)
+    launches = (1 if fused_ug else 2) + (1 if fused_dn else 2)
     out = {
         "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
-        "value": tokens_per_s,
-        "unit": "layer-tokens/s" if a.config == 2 else "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warm_steps,
-        "ms_per_step": wall / steps * 1e3,
+        "value": steps_per_s,
+        "unit": "layer-tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": f"BASELINE configs[{a.config - 1}]: {cfg.name}, d_model={d}, d_ff={f}, "
                         f"{cfg.dtype} weights, batch 1, keep ratio {r} (k_in={k_in}, k_mid={k_mid}), "
-                        + (f"DIP-CA LRU cache frac {frac}, gamma {cfg.gamma}" if use_cache else "DIP only")
+                        + (f"DIP-CA {a.policy.upper()} cache frac {frac} (C_in={C_in}, C_mid={C_mid}), gamma {gamma}"
+                           if use_cache else "DIP only")
                         + f", {L} " + ("distinct weight copies visited round-robin" if a.config == 2
-                                        else "layers per token"),
+                                        else "layers per token, walked token-major"),
             "inputs": cfg.inputs, "weights_dtype": cfg.dtype,
             "weight_bytes_resident": int(L * bytes_of(3 * d * f)),
             "gathered_bytes_per_step": gathered,
-            "step": "one token through one MLP layer (4 kernel launches)" if B == 1 else
-                    f"{B} rows through one MLP layer (unioned column reads)",
-            "batch": B,
-            "launch": launch_mode,
+            "step": f"one token through one MLP layer ({launches} kernel launches"
+                    + (", cache updates of a token's layers batched into one more" if use_cache else "") + ")",
+            "batch": 1,
+            "launch": "launches issued from the host through dip_swiglu_mlp_forward_stack",
         },
-        "end_to_end_GBps": gathered * steps / wall / 1e9,
+        "timing": {"repeats": len(times), "blocks_per_repeat": blocks, "steps_per_block": K,
+                   "repeat_ms": [t * 1e3 for t in times], "statistic": "median of repeats",
+                   "pilot_block_ms": pilot * 1e3},
+        "tokens_per_s": steps_per_s / L if a.config != 2 else None,
+        "layers_per_token": L if a.config != 2 else None,
+        "end_to_end_GBps": gathered * steps_per_s / 1e9,
+        "end_to_end_frac_of_peak": gathered * steps_per_s / 1e9 / HBM_PEAK_GBS,
         "setup_s": t_setup,
     }
+    if use_cache:
+        _, (hi, hm) = hit_rates(D, cins, cmids, hr_before)
+        out["cache_hit_rate"] = {"in": hi, "mid": hm, "policy": a.policy, "gamma": gamma,
+                                 "window": "the timed repeats"}
 
     if a.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read
@@ -506,65 +566,213 @@ def main():
         del src, dst
 
     # ---- per-kernel durations from HIP events bound to the dispatches ---------------------
+    ceiling = None
     if not a.no_kernel_events:
-        n_prof = min(passes, max(1, 2048 // L))
-        D.dip_profile_enable(5 * L * n_prof + 16)
-        for t in range(n_prof):
-            run_pass(passes_w + passes + t)
+        n_prof = min(max(K, 4 * L), 4096)
+        D.dip_profile_enable(5 * n_prof + 64)
+        run.run(n_prof)
         torch.cuda.synchronize()
-        prof = {k: D.dip_profile_read(i) for i, k in
-                enumerate(("select_in", "gemv_upgate", "select_mid", "gemv_down"))}
-        try:
-            prof["cache_update_tail"] = D.dip_profile_read(7)   # one per stack call, when caches are on
-        except D.DipError:
-            pass
+        names = ("select_in", "gemv_upgate", "select_mid", "gemv_down")
+        prof = {k: D.dip_profile_read(i) for i, k in enumerate(names)}
+        prof["cache_updates"] = D.dip_profile_read(7)
         D.dip_profile_disable()
         out["kernels_us"] = {k: (v[0] / v[1] * 1e3 if v[1] else None) for k, v in prof.items()}
+        out["launches_per_step"] = sum(v[1] for v in prof.values()) / n_prof
+        # a plain streaming read of 4 GiB in the same run: the ceiling a load-only kernel reaches here
+        buf = torch.zeros(1 << 30, dtype=torch.int32, device="cuda")
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        D.dip_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        D.dip_profile_enable(16)
+        for _ in range(5):
+            D.dip_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        ms, n = D.dip_profile_read(8)
+        D.dip_profile_disable()
+        ceiling = buf.numel() * 4 / (ms / n * 1e-3) / 1e9
+        del buf
+        shape_ug = fused_ug or D.dip_gemv_launch_shape(mlps[0].w_ug, k_in, bundled=True)
+        shape_dn = fused_dn or D.dip_gemv_launch_shape(mlps[0].w_d, k_mid, bundled=False)
+        out["launch_shapes"] = {"gemv_upgate": list(shape_ug), "gemv_down": list(shape_dn),
+                                "fields": "lanes_per_row, waves, ksplit, unroll",
+                                "selection_inside_the_product": [bool(fused_ug), bool(fused_dn)]}
         ug_ms, ug_n = prof["gemv_upgate"]
         dn_ms, dn_n = prof["gemv_down"]
-        shape_ug = D.dip_gemv_launch_shape(mlps[0].w_ug, k_in, bundled=True)
-        shape_dn = D.dip_gemv_launch_shape(mlps[0].w_d, k_mid, bundled=False)
-        out["launch_shapes"] = {"gemv_upgate": list(shape_ug), "gemv_down": list(shape_dn),
-                                "fields": "lanes_per_row, waves, ksplit, unroll"}
         if ug_n:
             ach = ug_bytes / (ug_ms / ug_n * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": ach / HBM_PEAK_GBS,
                                "traffic": measured_traffic(cfg.name, r, shape_ug),
-                               "kernel": "gemv_kernel (up/gate + SwiGLU)",
+                               "kernel": ("fused_kernel (scores + top-K + gathered up/gate + SwiGLU in one launch)"
+                                          if fused_ug else "gemv_kernel (up/gate + SwiGLU)"),
                                "algorithmic_bytes_per_launch": ug_bytes,
-                               "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n}
-            if dn_n:
-                out["roofline_down"] = {"achieved": dn_bytes / (dn_ms / dn_n * 1e-3) / 1e9,
-                                        "algorithmic_bytes_per_launch": dn_bytes,
-                                        "avg_launch_us": dn_ms / dn_n * 1e3}
-    if use_cache:
-        hi = sum(c.meta_host()["cum_hits"] for c in cins)
-        lo = sum(c.meta_host()["cum_lookups"] for c in cins)
-        hm = sum(c.meta_host()["cum_hits"] for c in cmids)
-        lm = sum(c.meta_host()["cum_lookups"] for c in cmids)
-        out["cache_hit_rate"] = {"in": hi / max(lo, 1), "mid": hm / max(lm, 1)}
+                               "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n,
+                               "ceiling_GBps": ceiling, "frac_of_ceiling": ach / ceiling}
+        if dn_n:
+            ach = dn_bytes / (dn_ms / dn_n * 1e-3) / 1e9
+            out["roofline_down"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": ach / HBM_PEAK_GBS,
+                                    "kernel": ("fused_kernel (scores + top-K + gathered down in one launch)"
+                                               if fused_dn else "gemv_kernel (down)"),
+                                    "algorithmic_bytes_per_launch": dn_bytes,
+                                    "avg_launch_us": dn_ms / dn_n * 1e3, "launches": dn_n,
+                                    "ceiling_GBps": ceiling, "frac_of_ceiling": ach / ceiling}
+
+    # ---- eviction policies and the penalty, on fresh caches (Sec. 6.4), and what the measured hit
+    #      rates mean on the paper's simulated phone (Sec. 6.1, App. A) --------------------------
+    if use_cache and not a.no_side_runs:
+        side = {}
+        n_side, n_skip = a.side_tokens, a.side_tokens // 3
+        # int4 column sizes of this shape: the paper's throughput runs are INT4
+        col_in, col_mid = 2 * (f // 2 + (f // 128) * 2), d // 2 + (d // 128) * 2
+        mlp_bytes = L * (d * col_in + f * col_mid)
+        static_bytes = max(0.0, 7.4e9 - mlp_bytes) if a.config in (4, 5) else 0.0
+        for pol_name in ("lru", "lfu"):
+            for g in (1.0, gamma):
+                ci, cm = fresh_caches({"lru": D.DIP_LRU, "lfu": D.DIP_LFU}[pol_name])
+                rr = Runner(ci, cm, g)
+                rr.run(n_skip * L)
+                torch.cuda.synchronize()
+                before = hit_rates(D, ci, cm)[0]
+                rr.run((n_side - n_skip) * L)
+                torch.cuda.synchronize()
+                _, (hi, hm) = hit_rates(D, ci, cm, before)
+                sim = twotier.sparse_tokens_per_second(static_bytes, L, col_in, col_mid, k_in, k_mid, hi, hm)
+                side[f"{pol_name}_gamma{g:g}"] = {"hit_rate_in": hi, "hit_rate_mid": hm,
+                                                  "simulated_mobile_tokens_per_s": sim}
+                del rr, ci, cm
+        out["eviction_policies"] = {
+            "runs": side,
+            "procedure": f"fresh caches, {n_side} tokens through all {L} layers, hit rates over the last "
+                         f"{n_side - n_skip}; gamma 1 is plain DIP (keys |x|)",
+            "mobile_model": "bytes missed / 1 GB/s Flash against bytes used / 60 GB/s DRAM (Sec. 6.1), INT4 column "
+                            f"sizes of this shape, {static_bytes / 1e9:.2f} GB of never-pruned weights pinned in DRAM",
+            "paper_table2_phi3_medium_context": PAPER_TABLE2_PHI3_MEDIUM,
+        }
 
     # ---- the oracle on the host cores, bounded sample --------------------------------------
     if not a.no_cpu_baseline:
         from oracle import dip_oracle as O
-        w0 = host_w[0]
         nt = a.cpu_sample_tokens
-        oc_in = O.CacheState(n=d, capacity=C_in) if use_cache else None
-        oc_mid = O.CacheState(n=f, capacity=C_mid) if use_cache else None
+        oc_in = O.CacheState(n=d, capacity=C_in, policy=a.policy) if use_cache else None
+        oc_mid = O.CacheState(n=f, capacity=C_mid, policy=a.policy) if use_cache else None
         c0, w0t = time.process_time(), time.perf_counter()
         for t in range(nt):
-            O.mlp_forward(w0["ug"], w0["d"], X[t % n_tok, 0], k_in, k_mid, oc_in, oc_mid, cfg.gamma)
+            O.mlp_forward(host0["ug"], host0["d"], X[t % n_tok, 0], k_in, k_mid, oc_in, oc_mid, gamma)
         wall_o = time.perf_counter() - w0t
         cpu_o = time.process_time() - c0
-        per_s = nt / wall_o
         out["cpu_baseline"] = {
-            "value": per_s if a.config == 2 else per_s / L,
-            "unit": out["unit"], "cores": max(1, int(round(cpu_o / wall_o))), "kind": "oracle",
+            "value": nt / wall_o, "unit": out["unit"], "cores": max(1, int(round(cpu_o / wall_o))),
+            "kind": "oracle",
             "sample": f"{nt} tokens through layer 0 of the same workload "
-                      f"({wall_o:.1f} s wall, {cpu_o:.1f} s CPU; "
-                      + ("" if a.config == 2 else f"per-token rate extrapolated to {L} layers; ")
-                      + f"host has {len(os.sched_getaffinity(0))} usable cores)"}
+                      f"({wall_o:.1f} s wall, {cpu_o:.1f} s CPU; host has {len(os.sched_getaffinity(0))} usable cores)"}
+    print(json.dumps(out))
+
+
+def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gamma, k_in, k_mid, t_setup):
+    """Config 5 at batch B > 1: B rows per step through one layer, columns read once per step
+    if any row selected them.  Bytes are the MEASURED union sizes times the column sizes."""
+    import numpy as np
+    import statistics
+    import torch
+
+    d, f = cfg.d_model, cfg.d_ff
+    n_tok = Xd.shape[0]
+    use_cache = cins is not None
+    # row b of layer l at step t is its own stream: shifted copies of the layer's stream
+    Xb = torch.stack([Xd[(torch.arange(n_tok) + 37 * b) % n_tok] for b in range(B)], dim=2).contiguous()
+    Yb = torch.empty(L, B, d, dtype=torch.float32, device="cuda")
+    ws = torch.empty(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[0], B, k_in, k_mid),
+                     dtype=torch.uint8, device="cuda")
+    wd, wf = (d + 31) // 32, (f + 31) // 32
+    m_in = torch.zeros(B, wd, dtype=torch.int32, device="cuda")
+    m_mid = torch.zeros(B, wf, dtype=torch.int32, device="cuda")
+    pos = [0]
+
+    def run(n, masks=False):
+        for _ in range(n):
+            t, l = divmod(pos[0], L)
+            D.dip_swiglu_mlp_forward_batched(mlps[l], Xb[t % n_tok, l], B, k_in, k_mid,
+                                             cins[l] if use_cache else None, cmids[l] if use_cache else None,
+                                             gamma, Yb[l], m_in if masks else None, None, m_mid if masks else None, ws)
+            pos[0] += 1
+
+    K, W = max(1, a.steps), max(0, a.warmup)
+    run(W)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+    t0 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    pilot = time.perf_counter() - t0
+    blocks = max(1, int(np.ceil(a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
+    times = []
+    for _ in range(max(1, a.repeats)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(blocks):
+            run(K)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+    wall = statistics.median(times)
+    ms_per_step = wall / (blocks * K) * 1e3
+
+    # measured union sizes: |U_in|, |U_mid| averaged over sample steps
+    def popcount_union(m):
+        u = m[0]
+        for b in range(1, B):
+            u = u | m[b]
+        return int(np.unpackbits(u.cpu().numpy().view(np.uint8)).sum())
+    ns, u_in, u_mid = 32, 0, 0
+    for _ in range(ns):
+        run(1, masks=True)
+        torch.cuda.synchronize()
+        u_in += popcount_union(m_in)
+        u_mid += popcount_union(m_mid)
+    u_in, u_mid = u_in / ns, u_mid / ns
+    col_in, col_mid = 2 * (f // 2 + (f // 128) * 2), d // 2 + (d // 128) * 2
+    ug_bytes, dn_bytes = u_in * col_in, u_mid * col_mid
+    gathered = ug_bytes + dn_bytes
+
+    n_prof = min(K, 512)
+    D.dip_profile_enable(12 * n_prof + 64)
+    run(n_prof)
+    torch.cuda.synchronize()
+    names = ("select_in", "gemv_upgate", "select_mid", "gemv_down")
+    prof = {k: D.dip_profile_read(i) for i, k in enumerate(names)}
+    D.dip_profile_disable()
+    ug_ms, ug_n = prof["gemv_upgate"]
+    dn_ms, dn_n = prof["gemv_down"]
+    ach = ug_bytes / (ug_ms / ug_n * 1e-3) / 1e9
+    out = {
+        "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
+        "value": B * 1e3 / ms_per_step, "unit": "row-layers/s (rows x layer-steps per second)",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"BASELINE configs[{a.config - 1}]: {cfg.name}, d_model={d}, d_ff={f}, {cfg.dtype} weights, "
+                        f"batch {B} (per-row top-K masks, unioned column reads), keep ratio {r} "
+                        f"(k_in={k_in}, k_mid={k_mid}), "
+                        + (f"DIP-CA {a.policy.upper()} cache frac {frac}, gamma {gamma}" if use_cache else "DIP only")
+                        + f", {L} layers per token, walked token-major",
+            "inputs": cfg.inputs, "weights_dtype": cfg.dtype, "batch": B,
+            "measured_union_columns": {"in": u_in, "mid": u_mid, "of": [d, f], "sample_steps": ns},
+            "gathered_bytes_per_step": gathered,
+            "step": f"{B} rows through one MLP layer (dip_swiglu_mlp_forward_batched)",
+        },
+        "timing": {"repeats": len(times), "blocks_per_repeat": blocks, "steps_per_block": K,
+                   "repeat_ms": [t * 1e3 for t in times], "statistic": "median of repeats"},
+        "tokens_per_s": B * 1e3 / ms_per_step / L,
+        "end_to_end_GBps": gathered / (ms_per_step * 1e-3) / 1e9,
+        "setup_s": t_setup,
+        "kernels_us": {k: (v[0] / v[1] * 1e3 if v[1] else None) for k, v in prof.items()},
+        "roofline": {"bound": "hbm" if B <= 2 else "mfma", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "batched gathered product (up/gate), bytes of the measured union",
+                     "algorithmic_bytes_per_launch": ug_bytes, "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n},
+        "roofline_down": {"achieved": dn_bytes / (dn_ms / dn_n * 1e-3) / 1e9, "algorithmic_bytes_per_launch": dn_bytes,
+                          "avg_launch_us": dn_ms / dn_n * 1e3},
+    }
     print(json.dumps(out))
 
 

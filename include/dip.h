@@ -8,14 +8,17 @@
  *   GLU(x)   = W^u x (.) SiLU(W^g x)                                   (Sec. 3, Eq. 2)
  *   m        binary column mask with exactly k ones, m = topK(s, k)    (Alg. 1)
  *   c        binary residency mask: which columns are in the cache     (Sec. 5.2)
- *   s        = |x| (c + gamma (1 - c)) / ||x||_inf                     (Sec. 5.2, Eq. 6)
+ *   s        = |x| (c + gamma (1 - c)) / ||x||_inf                     (Sec. 5.2, Eq. 10)
  *
  * Conventions
  *   - Plain C ABI.  Every pointer is a DEVICE pointer unless its comment says "host".
  *     Descriptor structs (dip_weight, dip_cache, dip_mlp, dip_debug) are host structs
  *     holding device pointers; the library reads them during the call only.
- *   - The library allocates nothing on the device and keeps no device state: outputs,
- *     cache state and workspace belong to the caller.  It never frees caller memory.
+ *   - The library allocates nothing on the device: outputs, cache state and workspace
+ *     belong to the caller, and it never frees caller memory.  The calls declared in this
+ *     header keep no state between calls, with one exception that says so
+ *     (dip_swiglu_mlp_forward_noalloc and its built-in scratch).  The process-wide
+ *     switches for tuning and per-kernel timing live in dip_devtools.h.
  *   - All work is enqueued on the caller's stream (a hipStream_t passed as void*, NULL =
  *     the default stream).  No call synchronises with the host or reads device memory
  *     back.  Calls on one stream are ordered; calls that share a workspace or a cache on
@@ -178,7 +181,7 @@ int32_t dip_version(void);
 const char* dip_last_error(void);
 
 /*
- * Cache-aware scores, Sec. 5.2 Eq. 6 / Alg. 1 step 1, in fp32 with this exact operation
+ * Cache-aware scores, Sec. 5.2 Eq. 10 / Alg. 1 step 1, in fp32 with this exact operation
  * order (round to nearest even, no fused operations, denormals kept):
  *     a = |x_i| ;  p = c_i ? a : fl(a * gamma) ;  s_i = fl(p / M),  M = max_i |x_i| ;
  *     M == 0  ->  s = 0.
@@ -215,7 +218,7 @@ int32_t dip_cache_init(const dip_cache* cache, const uint32_t* initial_bits, voi
  *   free   = capacity - |c| ;  victims V = c & ~m  (a column this token uses is never evicted)
  *   n_ins  = min(|misses|, free + |V|) ;  evict the max(0, n_ins - free) members of V with
  *            the smallest (stamp, index) ;  insert the first n_ins misses ;  the remaining
- *            misses bypass the cache (Sec. 6.3: when the active set does not fit, part of
+ *            misses bypass the cache (Sec. 6.4: when the active set does not fit, part of
  *            it is used without being cached).
  *   LFU: stamp counts every selection of a column, resident or not, and survives eviction.
  * Advances meta[DIP_META_STEP] and refreshes the other meta counters.
@@ -256,7 +259,7 @@ int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* id
  *   3. s2 = score(h~, c_mid)        m2 = topK(s2, k_mid)      c_mid <- cache_update(c_mid, m2)
  *   4. y  = sum_{i in m2} W^d[:,i] h~_i
  * Scoring uses the cache state from before this token (the paper's c^(t-1)).  With a NULL
- * cache the key is |.| (DIP); a cache pointer switches that point to Eq. 6 (DIP-CA) and its
+ * cache the key is |.| (DIP); a cache pointer switches that point to Eq. 10 (DIP-CA) and its
  * state is updated in place.
  *   x      d_model floats       y_out   d_model floats
  *   1 <= k_in <= d_model, 1 <= k_mid <= d_ff;  d_model, d_ff <= DIP_MAX_N
@@ -289,16 +292,22 @@ int32_t dip_swiglu_mlp_forward_noalloc(const dip_mlp* mlp, const float* x, int32
 /*
  * The same forward for n_layers independent layers in one call (a decode step over a
  * stack): layer l reads x + l * x_stride and writes y_out + l * y_stride (strides in
- * floats).  mlps / caches_in / caches_mid are host arrays of n_layers descriptors; the
- * cache arrays may be NULL (DIP) .  All layers share one workspace sized for the largest.
- * Every layer needs cache descriptors of its own: the update of one layer's point-2 cache
- * runs next to the following layer's kernels.
+ * floats) and keeps k_in[l] of its inputs and k_mid[l] of its GLU units (host arrays of
+ * n_layers entries: Sec. 4 allows different sparsity levels per matrix and layer).
+ * mlps / caches_in / caches_mid are host arrays of n_layers descriptors; the cache arrays
+ * may be NULL (DIP).  Every layer and pruning point needs a dip_cache of its own (the call
+ * rejects shared state): all caches are scored in their layers' launches and updated
+ * together in one launch at the end of the call.
+ * ws: dip_swiglu_mlp_forward_stack_workspace_bytes() bytes, 256-aligned.
  */
+size_t dip_swiglu_mlp_forward_stack_workspace_bytes(const dip_mlp* mlps, int32_t n_layers,
+                                                    const int32_t* k_in /* host */,
+                                                    const int32_t* k_mid /* host */);
 int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,
-                                     int64_t x_stride, int32_t k_in, int32_t k_mid,
-                                     const dip_cache* caches_in, const dip_cache* caches_mid,
-                                     float gamma, float* y_out, int64_t y_stride, void* ws,
-                                     size_t ws_bytes, void* stream);
+                                     int64_t x_stride, const int32_t* k_in /* host */,
+                                     const int32_t* k_mid /* host */, const dip_cache* caches_in,
+                                     const dip_cache* caches_mid, float gamma, float* y_out,
+                                     int64_t y_stride, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * A small decode batch through one layer: `batch` (1..8) rows X[b] (row stride d_model)
@@ -311,9 +320,13 @@ int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, cons
  *   mask_in_out   [batch][ceil(d_model/32)] words     h_out  [batch][d_ff] floats
  *   mask_mid_out  [batch][ceil(d_ff/32)] words
  * Summation order is fixed by the launch configuration (bit-repeatable).
- * DIP_INT4_G128 weights with batch >= 3 are multiplied on the matrix cores: activation times
- * group scale enters as two fp16 terms (22 significant bits) and must stay below the fp16
- * range, |x * scale| < 65504; the sums are fp32 as everywhere else.
+ * DIP_INT4_G128 weights with batch >= 3 are multiplied on the matrix cores (matrices of up to
+ * 4 GiB; larger ones take the vector path): every row's activations are first scaled by a
+ * power of two into [8, 16) -- exact, and undone exactly on the partial sums, so the result
+ * does not depend on the magnitude of the activations -- and activation times group scale
+ * enters as two fp16 terms (about 21 significant bits of the row's largest product); this
+ * needs group scales of at most 4094 (|w| up to 28658; beyond that the sums overflow to
+ * inf).  The sums are fp32 as everywhere else.
  */
 size_t dip_swiglu_mlp_forward_batched_workspace_bytes(const dip_mlp* mlp, int32_t batch,
                                                       int32_t k_in, int32_t k_mid);
@@ -366,7 +379,7 @@ int32_t dip_partial_pruning_forward(const dip_mlp_split* mlp, int32_t scheme, co
  * cache update the inserted columns take over the slots of the evicted ones (i-th inserted,
  * ascending, <- slot of the i-th evicted; the rest get slots never used before), their rows
  * are copied host -> HBM, and the gathered product reads resident columns from their slots
- * and the misses that found no room (Sec. 6.3) straight from host memory.  y is bit-identical
+ * and the misses that found no room (Sec. 6.4) straight from host memory.  y is bit-identical
  * to dip_swiglu_mlp_forward on the same inputs and cache states.
  */
 size_t dip_tier_init_workspace_bytes(const dip_tiered_weight* tw);
@@ -377,47 +390,6 @@ int32_t dip_tiered_mlp_forward(const dip_tiered_mlp* mlp, const float* x, int32_
                                const dip_cache* cache_in, const dip_cache* cache_mid, float gamma,
                                float* y_out, const dip_debug* dbg, void* ws, size_t ws_bytes,
                                void* stream);
-
-/*
- * Launch-shape override for the gathered GEMV kernels, for tuning sweeps.  0 restores the
- * built-in choice for that parameter.  Host-side, process-wide, not thread-safe against
- * concurrent launches.
- *   lanes_per_row  8, 16, 32 or 64 lanes cooperate on one stored row (16 bytes per lane)
- *   waves          wavefronts per workgroup: 2, 4, 8 or 16
- *   ksplit         workgroups that share one output strip (partial sums reduced in fixed order)
- *   unroll         rows in flight per lane group: 1, 2, 4 or 8
- */
-int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll);
-
-/*
- * The launch shape the gathered GEMV would use for matrix w and k selected rows, for
- * reports: shape_out (host, 4 ints) = {lanes_per_row, waves, ksplit, unroll}.
- * bundled != 0 asks for the up/gate kernel of dip_swiglu_mlp_forward (w = the bundled
- * matrix, two output halves per workgroup), 0 for the plain kernel.
- */
-int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out);
-
-/*
- * Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is
- * bracketed by a pair of HIP events bound to that dispatch (its own begin/end timestamps,
- * no extra work on the stream), up to max_launches launches; later launches are not timed.
- * The events are host objects; no device memory is allocated.  dip_profile_read() waits
- * for the recorded events and returns the summed duration and the number of launches of
- * one kernel kind.  Process-wide and not thread-safe: meant for a single benchmarking
- * thread.
- */
-#define DIP_KERNEL_SELECT_IN 0   /* scores + top-K + cache update at pruning point 1       */
-#define DIP_KERNEL_GEMV_UPGATE 1 /* gathered up/gate GEMV + SwiGLU                          */
-#define DIP_KERNEL_SELECT_MID 2  /* scores + top-K + cache update at pruning point 2       */
-#define DIP_KERNEL_GEMV_DOWN 3   /* gathered down GEMV (also dip_gathered_gemv)             */
-#define DIP_KERNEL_GEMV_DENSE 4  /* dense first product of gate / up pruning                */
-#define DIP_KERNEL_ROWDOT 5      /* row-gathered dot products                               */
-#define DIP_KERNEL_TIER_FILL 6   /* host -> HBM copies of the columns a cache update inserted  */
-#define DIP_KERNEL_CACHE_UPDATE 7 /* a cache update launched on its own (end of a forward call) */
-#define DIP_KERNEL_KINDS 8
-int32_t dip_profile_enable(int32_t max_launches);
-int32_t dip_profile_read(int32_t kind, double* total_ms /* host */, int32_t* launches /* host */);
-int32_t dip_profile_disable(void);
 
 #ifdef __cplusplus
 }

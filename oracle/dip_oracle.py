@@ -14,7 +14,7 @@ procedure taken step by step in the paper's order:
   Sec. 3, Eq. 3     the sparse MLP uses column-masked W~^u, W~^g, W~^d
   Sec. 4 (DIP)      mask 1 = topK(|x|) removes columns of W^u and W^g;
                     mask 2 = topK(|GLU~(x)|) removes columns of W^d
-  Sec. 5.2, Eq. 6   s = |x| (c + gamma (1 - c)) / ||x||_inf
+  Sec. 5.2, Eq. 10   s = |x| (c + gamma (1 - c)) / ||x||_inf
   Sec. 5.2, Alg. 1  s -> m = topK(s, k) -> c' = cache_update(c, m) -> W~ = W (.) m
 
 Arithmetic.  Scores are fp32, in exactly this operation order, round to
@@ -88,13 +88,13 @@ def n_cols(w) -> int:
 
 
 # ---------------------------------------------------------------------------
-# Sec. 5.2 Eq. 6 / Alg. 1 step 1: scores
+# Sec. 5.2 Eq. 10 / Alg. 1 step 1: scores
 # ---------------------------------------------------------------------------
 def score(v: np.ndarray, cache_bits: Optional[np.ndarray], gamma: float) -> np.ndarray:
     """Selection key for every feature.
 
     cache_bits None  ->  plain DIP key |v| (Sec. 4).
-    otherwise        ->  Eq. 6 with c = cache_bits (bool[n]), all in fp32.
+    otherwise        ->  Eq. 10 with c = cache_bits (bool[n]), all in fp32.
     """
     v = np.asarray(v, dtype=F32)
     a = np.abs(v)
@@ -182,7 +182,7 @@ def cache_update(st: CacheState, mask: np.ndarray) -> dict:
       n_ins      = min(|Mi|, free + |V|)
       evict the (n_ins - free)+ members of V with the smallest (priority, index)
       insert the first n_ins members of Mi; the rest bypass the cache
-      (Sec. 6.3: with too little room part of the active set goes straight
+      (Sec. 6.4: with too little room part of the active set goes straight
       to the processing unit).
 
     Priority: LRU -> stamp = step of last use.  LFU -> stamp = use count; it

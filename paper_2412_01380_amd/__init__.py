@@ -11,9 +11,9 @@ from .libdip import (  # noqa: F401
     dip_ca_scores, dip_cache_init, dip_cache_update, dip_gathered_gemv,
     dip_gathered_gemv_workspace_bytes, dip_last_error, dip_prune_topk,
     dip_swiglu_mlp_forward, dip_swiglu_mlp_forward_stack, dip_swiglu_mlp_forward_noalloc,
-    DIP_STATIC_SCRATCH_BYTES,
+    DIP_STATIC_SCRATCH_BYTES, dip_swiglu_mlp_forward_stack_workspace_bytes,
     dip_swiglu_mlp_forward_workspace_bytes, dip_tune_gemv, dip_version, MlpStack, EXPORTS, META,
-    dip_gemv_launch_shape, dip_profile_enable,
+    dip_gemv_launch_shape, dip_profile_enable, dip_set_fusion, dip_fused_launch_shape, dip_stream_read,
     dip_cache_state_bytes, dip_cache_blob_bytes, dip_cache_export, dip_cache_import,
     TieredWeight, TieredMlp, dip_tier_init, dip_tier_init_workspace_bytes, dip_tiered_mlp_forward,
     dip_tiered_mlp_forward_workspace_bytes,

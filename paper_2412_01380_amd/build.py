@@ -11,6 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIBPATH = os.path.join(LIBDIR, "libdip.so")
 SOURCES = ["dip_api.hip", "dip_select.hip", "dip_gemv.hip", "dip_batched.hip", "dip_tier.hip"]
+# dip_fused.hip is compiled once per (segments, weight type): six objects built in parallel
+FUSED_VARIANTS = [(nseg, dtype) for nseg in (1, 2) for dtype in (0, 1, 2)]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -36,6 +38,15 @@ def build(verbose: bool = True) -> str:
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for nseg, dtype in FUSED_VARIANTS:
+        obj = os.path.join(objdir, f"dip_fused_{nseg}_{dtype}.o")
+        objs.append(obj)
+        cmd = [hipcc, *flags, f"-DDIP_FUSED_NSEG={nseg}", f"-DDIP_FUSED_DTYPE={dtype}",
+               "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, "dip_fused.hip"), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((f"dip_fused.hip[{nseg},{dtype}]",
+                      subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)

@@ -91,21 +91,20 @@ int32_t validate_gamma(float gamma) {
     return DIP_OK;
 }
 
-// ---- workspace layout of the fused forward ------------------------------------------------
+// ---- workspace layout of the forward calls ---------------------------------------------------
+// [ mask words of every layer: point 1, point 2 ]  kept until the cache updates at the end of the call
+// [ scratch of one layer, shared by all layers   ]  index lists, h~, partial sums, ticket counters
+constexpr size_t kMaskBytes = sizeof(uint32_t) * (DIP_MAX_N / 32);
+constexpr int kMaxCounters = 2048;   // strips of the two products of a layer, at the narrowest strip width
+
 struct ForwardPlan {
     int d, f;
-    GemvShape ug, dn;
-    int strips_ug, strips_dn;
-    size_t off_mask1, off_mask2[2], off_idx1, off_val1, off_h, off_idx2, off_val2, off_part_ug, off_part_dn, off_cnt;
-    size_t total;
-};
-
-// A cache update that no kernel of the current token waits for: it is handed to the next
-// selection launch as work for a second workgroup (or launched on its own at the end).
-struct PendingUpdate {
-    bool active = false;
-    int parity = 0;       // which of the two point-2 mask buffers the next layer writes
-    SelectParams p;
+    GemvShape ug, dn;          // selection and product launched apart
+    GemvShape fug, fdn;        // product with the selection at its head
+    bool fuse_ug, fuse_dn;
+    int strips_ug, strips_dn;  // ticket counters (the larger of the two launch shapes)
+    size_t off_idx1, off_val1, off_h, off_idx2, off_val2, off_part_ug, off_part_dn, off_cnt;
+    size_t total;              // scratch of the layer, without the mask words
 };
 
 ForwardPlan plan_forward(const dip_mlp* mlp, int k_in, int k_mid) {
@@ -114,24 +113,31 @@ ForwardPlan plan_forward(const dip_mlp* mlp, int k_in, int k_mid) {
     pl.f = mlp->w_d.n_in;
     pl.ug = choose_gemv_shape(mlp->w_ug.dtype, pl.f, 2, k_in);
     pl.dn = choose_gemv_shape(mlp->w_d.dtype, pl.d, 1, k_mid);
+    pl.fuse_ug = fused_shape(mlp->w_ug.dtype, pl.d, pl.f, 2, k_in, &pl.fug);
+    pl.fuse_dn = fused_shape(mlp->w_d.dtype, pl.f, pl.d, 1, k_mid, &pl.fdn);
     pl.strips_ug = gemv_strips(pl.ug, mlp->w_ug.dtype, pl.f);
     pl.strips_dn = gemv_strips(pl.dn, mlp->w_d.dtype, pl.d);
+    int ks_ug = pl.ug.ksplit, ks_dn = pl.dn.ksplit;
+    if (pl.fuse_ug) {
+        pl.strips_ug = std::max(pl.strips_ug, gemv_strips(pl.fug, mlp->w_ug.dtype, pl.f));
+        ks_ug = std::max(ks_ug, pl.fug.ksplit);
+    }
+    if (pl.fuse_dn) {
+        pl.strips_dn = std::max(pl.strips_dn, gemv_strips(pl.fdn, mlp->w_d.dtype, pl.d));
+        ks_dn = std::max(ks_dn, pl.fdn.ksplit);
+    }
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    // The mask buffers sit at the same place for every layer shape, and point 2 has two of
-    // them used in turn: the deferred cache update of one layer reads its mask while the
-    // next layer (maybe of another shape, with another plan) writes its own.
-    pl.off_mask1 = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
-    pl.off_mask2[0] = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
-    pl.off_mask2[1] = take(sizeof(uint32_t) * (DIP_MAX_N / 32));
+    // the ticket counters come first: they sit at the same place for every layer shape, are
+    // cleared once per call and return to zero with every launch that uses them
+    pl.off_cnt = take(sizeof(uint32_t) * kMaxCounters);
     pl.off_idx1 = take(sizeof(int32_t) * k_in);
     pl.off_val1 = take(sizeof(float) * k_in);
     pl.off_h = take(sizeof(float) * pl.f);
     pl.off_idx2 = take(sizeof(int32_t) * k_mid);
     pl.off_val2 = take(sizeof(float) * k_mid);
-    pl.off_part_ug = take(pl.ug.ksplit > 1 ? sizeof(float) * 2 * pl.f * pl.ug.ksplit : 0);
-    pl.off_part_dn = take(pl.dn.ksplit > 1 ? sizeof(float) * pl.d * pl.dn.ksplit : 0);
-    pl.off_cnt = take(sizeof(uint32_t) * (pl.strips_ug + pl.strips_dn));
+    pl.off_part_ug = take(ks_ug > 1 ? sizeof(float) * 2 * pl.f * ks_ug : 0);
+    pl.off_part_dn = take(ks_dn > 1 ? sizeof(float) * pl.d * ks_dn : 0);
     pl.total = o;
     return pl;
 }
@@ -153,22 +159,17 @@ int32_t validate_mlp(const dip_mlp* mlp, int k_in, int k_mid) {
     return DIP_OK;
 }
 
-// Launch order for one token of one layer with caches at both points:
-//   scores + top-K at point 1
-//   gathered up/gate product
-//   [scores + top-K at point 2 | cache update of point 1 | cache update of point 2 left over
-//    from the previous layer]          (three workgroups of one launch)
-//   gathered down product
-// and the cache update of point 2 is left pending.  A cache is scored with its state before
-// this token (the update of the same cache always comes in a later launch), and two launches
-// that touch the same cache are ordered by the stream.
+// One token through one layer.  Launches, with a product that runs its own selection:
+//   up/gate product   (scores + top-K of point 1 at its head)
+//   down product      (scores + top-K of point 2 at its head)
+// and otherwise selection and product apart (four launches).  Either way the masks go to the
+// layer's two mask buffers and the cache updates are left to the caller, which runs them all
+// in one launch at the end of the call: a cache is scored with its state from before this
+// token (Alg. 1 takes c^(t-1)), and the update is in place before the next call scores it.
 int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, int k_in, int k_mid,
                     const dip_cache* cin, const dip_cache* cmid, float gamma, float* y,
-                    const dip_debug* dbg, char* ws, hipStream_t stream, PendingUpdate& pending,
-                    bool dense_in = false) {
-    uint32_t* mask1 = reinterpret_cast<uint32_t*>(ws + pl.off_mask1);
-    uint32_t* mask2 = reinterpret_cast<uint32_t*>(ws + pl.off_mask2[pending.parity]);
-    pending.parity ^= 1;
+                    const dip_debug* dbg, char* ws, uint32_t* mask1, uint32_t* mask2, hipStream_t stream,
+                    std::vector<UpdatePiece>& updates, bool dense_in = false) {
     int32_t* idx1 = reinterpret_cast<int32_t*>(ws + pl.off_idx1);
     float* val1 = reinterpret_cast<float*>(ws + pl.off_val1);
     float* h = reinterpret_cast<float*>(ws + pl.off_h);
@@ -183,87 +184,82 @@ int32_t forward_one(const dip_mlp* mlp, const ForwardPlan& pl, const float* x, i
     if (dbg && dbg->h) h = dbg->h;
     if (dbg && dbg->mask_in) mask1 = dbg->mask_in;
     if (dbg && dbg->mask_mid) mask2 = dbg->mask_mid;
+    const bool want_mask1 = cin || (dbg && dbg->mask_in);
+    const bool want_mask2 = cmid || (dbg && dbg->mask_mid);
 
     auto update_of = [](const dip_cache* c, const uint32_t* mask) {
-        SelectParams u;
-        std::memset(&u, 0, sizeof(u));
-        u.n = c->n; u.k = 1; u.mask_in = mask;
-        u.c_bits = c->bits; u.c_stamp = c->stamp; u.c_meta = c->meta;
-        u.capacity = c->capacity; u.policy = c->policy;
+        UpdatePiece u;
+        u.mask = mask; u.bits = c->bits; u.stamp = c->stamp; u.meta = c->meta;
+        u.n = c->n; u.capacity = c->capacity; u.policy = c->policy; u.pad = 0;
         return u;
     };
 
     int32_t st = DIP_OK;
-    if (dense_in) {
-        // GLU pruning (Sec. 3.2): nothing is pruned at point 1, every stored row in order
-        st = check_hip(launch_zero_u32(cnt_ug, pl.strips_ug + pl.strips_dn, stream), "counter reset");
-        if (st) return st;
-    } else {
-        // point 1: scores and m1
-        SelectParams s1;
-        std::memset(&s1, 0, sizeof(s1));
-        s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
-        s1.s_out = dbg ? dbg->s_in : nullptr;
-        s1.mask_out = (cin || dbg) ? mask1 : nullptr;
-        if (!cin && dbg && !dbg->mask_in) s1.mask_out = nullptr;
-        s1.idx_out = idx1; s1.val_out = val1;
-        if (cin) s1.score_bits = cin->bits;
-        s1.zero_ptr = cnt_ug; s1.zero_n = pl.strips_ug + pl.strips_dn;
-        st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
-        if (st) return st;
-    }
-
-    // gathered up/gate GEMV + SwiGLU
     GemvParams g1;
     std::memset(&g1, 0, sizeof(g1));
     g1.w = mlp->w_ug.data; g1.row_stride = mlp->w_ug.row_stride_bytes;
     g1.scales = static_cast<const uint16_t*>(mlp->w_ug.scales); g1.scale_stride = mlp->w_ug.n_out / 128; g1.dtype = mlp->w_ug.dtype;
-    g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.idx = idx1; g1.val = val1; g1.k = k_in; g1.out = h;
-    if (dense_in) { g1.idx = nullptr; g1.val = x; }
+    g1.n_in = pl.d; g1.n_out = pl.f; g1.nseg = 2; g1.k = k_in; g1.out = h;
     g1.partial = part_ug; g1.counters = cnt_ug;
-    st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
-    if (st) return st;
-
-    // point 2: scores and m2, next to the cache update of point 1
-    SelectParams s2;
-    std::memset(&s2, 0, sizeof(s2));
-    s2.v = h; s2.n = pl.f; s2.k = k_mid; s2.gamma = gamma;
-    s2.s_out = dbg ? dbg->s_mid : nullptr;
-    s2.mask_out = (cmid || (dbg && dbg->mask_mid)) ? mask2 : nullptr;
-    s2.idx_out = idx2; s2.val_out = val2;
-    if (cmid) s2.score_bits = cmid->bits;
-    SelectParams u1;
-    const SelectParams* ride[2] = {nullptr, nullptr};
-    int n_ride = 0;
-    if (cin && !dense_in) {
-        u1 = update_of(cin, mask1);
-        ride[n_ride++] = &u1;
+    if (dense_in) {
+        // GLU pruning (Sec. 3.2): nothing is pruned at point 1, every stored row in order
+        // (in the launch shape DIP would use with k_in = d_model, so that both give the same bits)
+        g1.idx = nullptr; g1.val = x;
+        st = check_hip(launch_gemv(g1, pl.fuse_ug ? pl.fug : pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "dense GEMV (up/gate)");
+    } else if (pl.fuse_ug) {
+        FusedParams fp;
+        fp.g = g1;
+        fp.s.v = x; fp.s.n = pl.d; fp.s.score_bits = cin ? cin->bits : nullptr; fp.s.gamma = gamma;
+        fp.s.mask_out = want_mask1 ? mask1 : nullptr;
+        fp.s.idx_out = dbg ? dbg->idx_in : nullptr;
+        fp.s.s_out = dbg ? dbg->s_in : nullptr;
+        st = check_hip(launch_fused(fp, pl.fug, stream, DIP_KERNEL_GEMV_UPGATE), "up/gate product with selection");
+    } else {
+        SelectParams s1;
+        std::memset(&s1, 0, sizeof(s1));
+        s1.v = x; s1.n = pl.d; s1.k = k_in; s1.gamma = gamma;
+        s1.s_out = dbg ? dbg->s_in : nullptr;
+        s1.mask_out = want_mask1 ? mask1 : nullptr;
+        s1.idx_out = idx1; s1.val_out = val1;
+        if (cin) s1.score_bits = cin->bits;
+        st = check_hip(launch_select(s1, stream, DIP_KERNEL_SELECT_IN), "select (point 1)");
+        if (st) return st;
+        g1.idx = idx1; g1.val = val1;
+        st = check_hip(launch_gemv(g1, pl.ug, stream, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
     }
-    if (pending.active) ride[n_ride++] = &pending.p;
-    st = check_hip(launch_select(s2, stream, DIP_KERNEL_SELECT_MID, ride[0], ride[1]), "select (point 2)");
     if (st) return st;
-    pending.active = false;
+    if (cin && !dense_in) updates.push_back(update_of(cin, mask1));
 
-    // gathered down GEMV
     GemvParams g2;
     std::memset(&g2, 0, sizeof(g2));
     g2.w = mlp->w_d.data; g2.row_stride = mlp->w_d.row_stride_bytes;
     g2.scales = static_cast<const uint16_t*>(mlp->w_d.scales); g2.scale_stride = mlp->w_d.n_out / 128; g2.dtype = mlp->w_d.dtype;
-    g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.idx = idx2; g2.val = val2; g2.k = k_mid; g2.out = y;
+    g2.n_in = pl.f; g2.n_out = pl.d; g2.nseg = 1; g2.k = k_mid; g2.out = y;
     g2.partial = part_dn; g2.counters = cnt_dn;
-    st = check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
-    if (st) return st;
-    if (cmid) {
-        pending.p = update_of(cmid, mask2);
-        pending.active = true;
+    if (pl.fuse_dn) {
+        FusedParams fp;
+        fp.g = g2;
+        fp.s.v = h; fp.s.n = pl.f; fp.s.score_bits = cmid ? cmid->bits : nullptr; fp.s.gamma = gamma;
+        fp.s.mask_out = want_mask2 ? mask2 : nullptr;
+        fp.s.idx_out = dbg ? dbg->idx_mid : nullptr;
+        fp.s.s_out = dbg ? dbg->s_mid : nullptr;
+        st = check_hip(launch_fused(fp, pl.fdn, stream, DIP_KERNEL_GEMV_DOWN), "down product with selection");
+    } else {
+        SelectParams s2;
+        std::memset(&s2, 0, sizeof(s2));
+        s2.v = h; s2.n = pl.f; s2.k = k_mid; s2.gamma = gamma;
+        s2.s_out = dbg ? dbg->s_mid : nullptr;
+        s2.mask_out = want_mask2 ? mask2 : nullptr;
+        s2.idx_out = idx2; s2.val_out = val2;
+        if (cmid) s2.score_bits = cmid->bits;
+        st = check_hip(launch_select(s2, stream, DIP_KERNEL_SELECT_MID), "select (point 2)");
+        if (st) return st;
+        g2.idx = idx2; g2.val = val2;
+        st = check_hip(launch_gemv(g2, pl.dn, stream, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
     }
+    if (st) return st;
+    if (cmid) updates.push_back(update_of(cmid, mask2));
     return DIP_OK;
-}
-
-int32_t flush_pending(PendingUpdate& pending, hipStream_t stream) {
-    if (!pending.active) return DIP_OK;
-    pending.active = false;
-    return check_hip(launch_select(pending.p, stream, DIP_KERNEL_CACHE_UPDATE), "cache update (point 2)");
 }
 
 }  // namespace
@@ -421,17 +417,30 @@ int32_t dip_gathered_gemv(const dip_weight* w, const float* x, const int32_t* id
 
 size_t dip_swiglu_mlp_forward_workspace_bytes(const dip_mlp* mlp, int32_t k_in, int32_t k_mid) {
     if (validate_mlp(mlp, k_in, k_mid)) return 0;
-    return plan_forward(mlp, k_in, k_mid).total;
+    return 2 * kMaskBytes + plan_forward(mlp, k_in, k_mid).total;
 }
 
+size_t dip_swiglu_mlp_forward_stack_workspace_bytes(const dip_mlp* mlps, int32_t n_layers,
+                                                    const int32_t* k_in, const int32_t* k_mid) {
+    if (!mlps || !k_in || !k_mid || n_layers < 1) return 0;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (validate_mlp(&mlps[l], k_in[l], k_mid[l])) return 0;
+        need = std::max(need, plan_forward(&mlps[l], k_in[l], k_mid[l]).total);
+    }
+    return (size_t)n_layers * 2 * kMaskBytes + need;
+}
+
+// k_in / k_mid: one value per layer (k_stride = 1) or one for all (k_stride = 0)
 static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const float* x, int64_t x_stride,
-                               int32_t k_in, int32_t k_mid, const dip_cache* caches_in,
-                               const dip_cache* caches_mid, float gamma, float* y_out,
-                               int64_t y_stride, const dip_debug* dbg, void* ws, size_t ws_bytes,
-                               void* stream, bool dense_in = false) {
+                               const int32_t* k_in, const int32_t* k_mid, int k_stride,
+                               const dip_cache* caches_in, const dip_cache* caches_mid, float gamma,
+                               float* y_out, int64_t y_stride, const dip_debug* dbg, void* ws,
+                               size_t ws_bytes, void* stream, bool dense_in = false) {
     if (!mlps) return fail(DIP_ERR_INVALID_ARG, "forward: null mlp descriptor");
     if (n_layers < 1) return fail(DIP_ERR_INVALID_ARG, "forward: n_layers must be >= 1");
     if (!x || !y_out) return fail(DIP_ERR_INVALID_ARG, "forward: null x or y_out");
+    if (!k_in || !k_mid) return fail(DIP_ERR_INVALID_ARG, "forward: null k_in or k_mid");
     if (caches_in || caches_mid) {
         int32_t st = validate_gamma(gamma);
         if (st) return st;
@@ -440,37 +449,61 @@ static int32_t forward_checked(const dip_mlp* mlps, int32_t n_layers, const floa
         return fail(DIP_ERR_UNSUPPORTED, "forward: debug index lists must be 16-byte aligned");
     size_t need = 0;
     for (int l = 0; l < n_layers; ++l) {
-        int32_t st = validate_mlp(&mlps[l], k_in, k_mid);
+        int32_t st = validate_mlp(&mlps[l], k_in[l * k_stride], k_mid[l * k_stride]);
         if (st) return st;
         if (caches_in && (st = validate_cache(&caches_in[l], mlps[l].w_ug.n_in, "cache_in"))) return st;
         if (caches_mid && (st = validate_cache(&caches_mid[l], mlps[l].w_d.n_in, "cache_mid"))) return st;
-        const size_t t = plan_forward(&mlps[l], k_in, k_mid).total;
-        if (t > need) need = t;
+        need = std::max(need, plan_forward(&mlps[l], k_in[l * k_stride], k_mid[l * k_stride]).total);
     }
+    // Every cache is scored in its layer's launches and updated at the end of the call: two
+    // layers (or the two points of one layer) that shared a cache would score the second use
+    // against a state that lacks the first one's update.
+    {
+        std::vector<const uint32_t*> seen;
+        for (int l = 0; l < n_layers; ++l) {
+            if (caches_in) seen.push_back(caches_in[l].bits);
+            if (caches_mid) seen.push_back(caches_mid[l].bits);
+        }
+        std::sort(seen.begin(), seen.end());
+        if (std::adjacent_find(seen.begin(), seen.end()) != seen.end())
+            return fail(DIP_ERR_INVALID_ARG, "forward: two pruning points share one cache state (every layer "
+                                             "and point needs a dip_cache of its own)");
+    }
+    const size_t mask_bytes = (size_t)n_layers * 2 * kMaskBytes;
+    need += mask_bytes;
     if (!ws || ws_bytes < need || !aligned(ws, 256))
         return fail(DIP_ERR_WORKSPACE, "forward: workspace must be 256-aligned and >= %zu bytes", need);
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    PendingUpdate pending;
-    for (int l = 0; l < n_layers; ++l) {
-        const ForwardPlan pl = plan_forward(&mlps[l], k_in, k_mid);
-        int32_t st = forward_one(&mlps[l], pl, x + (int64_t)l * x_stride, k_in, k_mid,
-                                 caches_in ? &caches_in[l] : nullptr,
-                                 caches_mid ? &caches_mid[l] : nullptr, gamma,
-                                 y_out + (int64_t)l * y_stride, dbg, static_cast<char*>(ws), hs, pending,
-                                 dense_in);
-        if (st) {
-            flush_pending(pending, hs);   // keep the caches consistent with what was launched
-            return st;
-        }
+    char* base = static_cast<char*>(ws);
+    char* scratch = base + mask_bytes;
+    // the ticket counters of the products start at zero and return to zero with every launch
+    int32_t st = check_hip(launch_zero_u32(reinterpret_cast<uint32_t*>(scratch), kMaxCounters, hs), "counter reset");
+    if (st) return st;
+    std::vector<UpdatePiece> updates;
+    updates.reserve(2 * (size_t)n_layers);
+    for (int l = 0; l < n_layers && !st; ++l) {
+        const int ki = k_in[l * k_stride], km = k_mid[l * k_stride];
+        const ForwardPlan pl = plan_forward(&mlps[l], ki, km);
+        uint32_t* mask1 = reinterpret_cast<uint32_t*>(base + (size_t)(2 * l) * kMaskBytes);
+        uint32_t* mask2 = reinterpret_cast<uint32_t*>(base + (size_t)(2 * l + 1) * kMaskBytes);
+        st = forward_one(&mlps[l], pl, x + (int64_t)l * x_stride, ki, km,
+                         caches_in ? &caches_in[l] : nullptr, caches_mid ? &caches_mid[l] : nullptr, gamma,
+                         y_out + (int64_t)l * y_stride, dbg, scratch, mask1, mask2, hs, updates, dense_in);
     }
-    return flush_pending(pending, hs);
+    // (after a failed launch: the updates of what was launched keep the caches consistent with it)
+    if (!updates.empty()) {
+        const int32_t st2 = check_hip(launch_update_batch(updates.data(), (int)updates.size(), hs, DIP_KERNEL_CACHE_UPDATE),
+                                      "cache updates");
+        if (!st) st = st2;
+    }
+    return st;
 }
 
 int32_t dip_swiglu_mlp_forward(const dip_mlp* mlp, const float* x, int32_t k_in, int32_t k_mid,
                                const dip_cache* cache_in, const dip_cache* cache_mid, float gamma,
                                float* y_out, const dip_debug* dbg, void* ws, size_t ws_bytes,
                                void* stream) {
-    return forward_checked(mlp, 1, x, 0, k_in, k_mid, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
+    return forward_checked(mlp, 1, x, 0, &k_in, &k_mid, 0, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
                            ws_bytes, stream);
 }
 
@@ -508,7 +541,7 @@ int32_t dip_swiglu_mlp_forward_noalloc(const dip_mlp* mlp, const float* x, int32
                                        float gamma, float* y_out, const dip_debug* dbg, void* stream) {
     int32_t st = validate_mlp(mlp, k_in, k_mid);
     if (st) return st;
-    const size_t need = plan_forward(mlp, k_in, k_mid).total;
+    const size_t need = 2 * kMaskBytes + plan_forward(mlp, k_in, k_mid).total;
     if (need > (size_t)DIP_STATIC_SCRATCH_BYTES)
         return fail(DIP_ERR_WORKSPACE,
                     "dip_swiglu_mlp_forward_noalloc: this layer needs %zu bytes of scratch, the built-in "
@@ -516,23 +549,24 @@ int32_t dip_swiglu_mlp_forward_noalloc(const dip_mlp* mlp, const float* x, int32
                     need, (size_t)DIP_STATIC_SCRATCH_BYTES);
     void* ws = nullptr;
     if ((st = static_scratch(&ws))) return st;
-    return forward_checked(mlp, 1, x, 0, k_in, k_mid, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
+    return forward_checked(mlp, 1, x, 0, &k_in, &k_mid, 0, cache_in, cache_mid, gamma, y_out, 0, dbg, ws,
                            (size_t)DIP_STATIC_SCRATCH_BYTES, stream);
 }
 
 int32_t dip_swiglu_mlp_forward_stack(const dip_mlp* mlps, int32_t n_layers, const float* x,
-                                     int64_t x_stride, int32_t k_in, int32_t k_mid,
+                                     int64_t x_stride, const int32_t* k_in, const int32_t* k_mid,
                                      const dip_cache* caches_in, const dip_cache* caches_mid,
                                      float gamma, float* y_out, int64_t y_stride, void* ws,
                                      size_t ws_bytes, void* stream) {
-    return forward_checked(mlps, n_layers, x, x_stride, k_in, k_mid, caches_in, caches_mid, gamma,
+    return forward_checked(mlps, n_layers, x, x_stride, k_in, k_mid, 1, caches_in, caches_mid, gamma,
                            y_out, y_stride, nullptr, ws, ws_bytes, stream);
 }
 
 namespace {
 struct BatchedPlan {
     int d, f, wd, wf, k1max, k2max, g1, g2;
-    size_t off_m1, off_u1, off_idx1, off_val1, off_m2, off_u2, off_idx2, off_val2, off_cnt, off_h,
+    bool mc1, mc2;             // product on the matrix cores
+    size_t off_rmax, off_m1, off_u1, off_idx1, off_val1, off_m2, off_u2, off_idx2, off_val2, off_cnt, off_h,
         off_part;
     size_t total;
 };
@@ -542,10 +576,13 @@ BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
     pl.wd = (pl.d + 31) / 32; pl.wf = (pl.f + 31) / 32;
     pl.k1max = std::min(pl.d, B * k_in);
     pl.k2max = std::min(pl.f, B * k_mid);
-    pl.g1 = batched_shares(mlp->w_ug.dtype, B, 2 * pl.f, pl.k1max);
-    pl.g2 = batched_shares(mlp->w_d.dtype, B, pl.d, pl.k2max);
+    pl.mc1 = batched_on_matrix_cores(mlp->w_ug.dtype, B, mlp->w_ug.n_in, mlp->w_ug.row_stride_bytes);
+    pl.mc2 = batched_on_matrix_cores(mlp->w_d.dtype, B, mlp->w_d.n_in, mlp->w_d.row_stride_bytes);
+    pl.g1 = batched_shares(mlp->w_ug.dtype, B, 2 * pl.f, pl.k1max, pl.mc1);
+    pl.g2 = batched_shares(mlp->w_d.dtype, B, pl.d, pl.k2max, pl.mc2);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    pl.off_rmax = take(sizeof(uint32_t) * 16);     // per point: 8 row maxima
     pl.off_m1 = take(sizeof(uint32_t) * B * pl.wd);
     pl.off_u1 = take(sizeof(uint32_t) * pl.wd);
     // index and multiplier lists carry 16 spare entries: the product reads whole vectors
@@ -619,6 +656,8 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         sp.v = q.v; sp.n = q.n; sp.k = q.k; sp.gamma = gamma;
         sp.score_bits = q.cache ? q.cache->bits : nullptr;
         sp.mask_out = q.masks; sp.rows = batch; sp.v_row_stride = q.n; sp.words_row_stride = q.words;
+        uint32_t* rowmax = reinterpret_cast<uint32_t*>(base + pl.off_rmax) + 8 * pt;
+        sp.zero_ptr = rowmax; sp.zero_n = 8;       // the union kernel below takes maxima into it
         if ((st = check_hip(launch_select(sp, hs, q.kind, have_deferred ? &deferred : nullptr),
                             "forward_batched: select")))
             return st;
@@ -628,6 +667,8 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         std::memset(&up, 0, sizeof(up));
         up.masks = q.masks; up.words_stride = q.words; up.x = q.v; up.x_stride = q.n; up.n = q.n;
         up.batch = batch; up.union_words = q.uwords; up.uidx = q.uidx; up.uval = q.uval; up.count_out = q.count;
+        const bool mc = pt == 0 ? pl.mc1 : pl.mc2;
+        up.rowmax = mc ? rowmax : nullptr;
         if ((st = check_hip(launch_union(up, hs), "forward_batched: union"))) return st;
         // one cache update with the union mask
         if (q.cache) {
@@ -646,8 +687,8 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         gp.scales = static_cast<const uint16_t*>(w.scales); gp.scale_stride = w.n_out / 128;
         gp.dtype = w.dtype; gp.n_in = w.n_in; gp.n_out = w.n_out;
         gp.uidx = q.uidx; gp.uval = q.uval; gp.k_dev = q.count; gp.k_max = q.kmax; gp.batch = batch;
-        gp.partial = part;
-        if ((st = check_hip(launch_batched_gemv(gp, shares, hs, pt == 0 ? DIP_KERNEL_GEMV_UPGATE : DIP_KERNEL_GEMV_DOWN),
+        gp.partial = part; gp.rowmax = mc ? rowmax : nullptr;
+        if ((st = check_hip(launch_batched_gemv(gp, shares, mc, hs, pt == 0 ? DIP_KERNEL_GEMV_UPGATE : DIP_KERNEL_GEMV_DOWN),
                             "forward_batched: gathered product")))
             return st;
         BatchedReduceParams rp;
@@ -681,7 +722,8 @@ int32_t dip_glu_pruning_forward(const dip_mlp* mlp, const float* x, int32_t k, f
     if (dbg && (dbg->s_in || dbg->mask_in || dbg->idx_in))
         return fail(DIP_ERR_INVALID_ARG, "dip_glu_pruning_forward: there is no pruning point 1 to report");
     if (!aligned(x, 16)) return fail(DIP_ERR_UNSUPPORTED, "dip_glu_pruning_forward: x must be 16-byte aligned");
-    return forward_checked(mlp, 1, x, 0, mlp->w_ug.n_in, k, nullptr, nullptr, 0.f, y_out, 0, dbg, ws,
+    const int32_t k_all = mlp->w_ug.n_in;
+    return forward_checked(mlp, 1, x, 0, &k_all, &k, 0, nullptr, nullptr, 0.f, y_out, 0, dbg, ws,
                            ws_bytes, stream, true);
 }
 
@@ -981,11 +1023,12 @@ int32_t dip_tiered_mlp_forward(const dip_tiered_mlp* mlp, const float* x, int32_
         if (pt == 0) {
             g.n_out = pl.f; g.nseg = 2; g.out = h;
             g.partial = reinterpret_cast<float*>(base + pl.off_part_ug); g.counters = cnt_ug;
-            st = check_hip(launch_gemv(g, pl.ug, hs, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
+            // (the launch shapes of dip_swiglu_mlp_forward: the same sums in the same order)
+            st = check_hip(launch_gemv(g, pl.fuse_ug ? pl.fug : pl.ug, hs, DIP_KERNEL_GEMV_UPGATE), "gathered GEMV (up/gate)");
         } else {
             g.n_out = pl.d; g.nseg = 1; g.out = y_out;
             g.partial = reinterpret_cast<float*>(base + pl.off_part_dn); g.counters = cnt_dn;
-            st = check_hip(launch_gemv(g, pl.dn, hs, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
+            st = check_hip(launch_gemv(g, pl.fuse_dn ? pl.fdn : pl.dn, hs, DIP_KERNEL_GEMV_DOWN), "gathered GEMV (down)");
         }
         if (st) return st;
     }
@@ -1002,6 +1045,33 @@ int32_t dip_gemv_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, i
                                 : choose_gemv_shape(w->dtype, w->n_out, 1, k);
     shape_out[0] = s.lpr; shape_out[1] = s.waves; shape_out[2] = s.ksplit; shape_out[3] = s.unroll;
     return DIP_OK;
+}
+
+int32_t dip_set_fusion(int32_t on) {
+    if (on != 0 && on != 1) return fail(DIP_ERR_INVALID_ARG, "dip_set_fusion: 0 or 1");
+    g_fusion = on;
+    return DIP_OK;
+}
+
+int32_t dip_fused_launch_shape(const dip_weight* w, int32_t k, int32_t bundled, int32_t* shape_out) {
+    int32_t st = validate_weight(w, "dip_fused_launch_shape");
+    if (st) return st;
+    if (!shape_out) return fail(DIP_ERR_INVALID_ARG, "dip_fused_launch_shape: null output");
+    if (k < 1 || k > w->n_in) return fail(DIP_ERR_INVALID_ARG, "dip_fused_launch_shape: k must be in [1, n_in]");
+    if (bundled && (w->n_out % 2)) return fail(DIP_ERR_INVALID_ARG, "dip_fused_launch_shape: bundled matrix needs an even n_out");
+    GemvShape s;
+    if (!fused_shape(w->dtype, w->n_in, bundled ? w->n_out / 2 : w->n_out, bundled ? 2 : 1, k, &s))
+        return fail(DIP_ERR_UNSUPPORTED, "dip_fused_launch_shape: selection and product are launched apart for this shape");
+    shape_out[0] = s.lpr; shape_out[1] = s.waves; shape_out[2] = s.ksplit; shape_out[3] = s.unroll;
+    return DIP_OK;
+}
+
+int32_t dip_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+    if (!src || !sink) return fail(DIP_ERR_INVALID_ARG, "dip_stream_read: null pointer");
+    if (bytes < 16 || bytes % 16 || !aligned(src, 16))
+        return fail(DIP_ERR_INVALID_ARG, "dip_stream_read: buffer must be 16-byte aligned, a multiple of 16 bytes");
+    return check_hip(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream), DIP_KERNEL_STREAM_READ),
+                     "dip_stream_read");
 }
 
 int32_t dip_profile_disable(void) {

@@ -71,19 +71,32 @@ __global__ __launch_bounds__(kUnionThreads) void union_kernel(UnionParams p) {
     __syncthreads();
 
     const int w = blockIdx.x * kUnionWordsPerWg + (tid >> 5), bit = tid & 31;
-    if (w >= nwords) return;
     uint32_t rows = 0, uw = 0;    // bit b of rows: row b selected this feature
-    for (int b = 0; b < p.batch; ++b) {
+    for (int b = 0; b < p.batch && w < nwords; ++b) {
         const uint32_t m = p.masks[(size_t)b * p.words_stride + w];
         uw |= m;
         rows |= ((m >> bit) & 1u) << b;
     }
-    if (!rows) return;
-    const uint32_t pos = s_base[w] + (uint32_t)__popc(uw & ((1u << bit) - 1u));
-    const int i = w * 32 + bit;
-    p.uidx[pos] = i;
-    for (int b = 0; b < p.batch; ++b)
-        p.uval[(size_t)pos * p.batch + b] = ((rows >> b) & 1u) ? p.x[(size_t)b * p.x_stride + i] : 0.f;
+    if (rows) {
+        const uint32_t pos = s_base[w] + (uint32_t)__popc(uw & ((1u << bit) - 1u));
+        const int i = w * 32 + bit;
+        p.uidx[pos] = i;
+        for (int b = 0; b < p.batch; ++b) {
+            const float xv = ((rows >> b) & 1u) ? p.x[(size_t)b * p.x_stride + i] : 0.f;
+            p.uval[(size_t)pos * p.batch + b] = xv;
+        }
+    }
+    // largest |multiplier| of every row (bit patterns of non-negative floats order like
+    // integers): one integer atomic per wavefront and row, zero on entry
+    if (p.rowmax) {
+        for (int b = 0; b < p.batch; ++b) {
+            uint32_t a = 0u;
+            if ((rows >> b) & 1u) a = __float_as_uint(fabsf(p.x[(size_t)b * p.x_stride + w * 32 + bit]));
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) a = max(a, (uint32_t)__shfl_xor((int)a, off));
+            if (lane == 0 && a) atomicMax(&p.rowmax[b], a);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -318,10 +331,17 @@ __global__ __launch_bounds__(kBWaves * 64) void bgemv_kernel(BatchedGemvParams p
 // unpacking.  v_mfma_f32_16x16x16_f16 takes it instead: M = batch row (16, the rows past B are
 // zero), K = 16 listed columns, N = 16 stored columns.  The scale belongs to (u, 128-column
 // group), so it goes into the left operand next to the multiplier: m * scale enters as the
-// sum of two fp16 numbers (its rounded value and the rounded rest, 22 significant bits; each
-// tile is multiplied twice), which requires |m * scale| < 65504, the fp16 range.  The right
-// operand holds the codes q + 8 in [0, 15], exact in fp16.  Sums are fp32; the offset leaves
-// as  -8 * sum_u m*scale, which a product with an all-ones right operand supplies.
+// sum of two fp16 numbers (its rounded value and the rounded rest; each tile is multiplied
+// twice).  fp16 has a fixed range, and the re-weighting of Sec. 5.2 normalises by ||x||_inf
+// precisely so that the dynamic range of the activations does not matter: every batch row is
+// therefore multiplied by the power of two that brings its largest |multiplier| into [8, 16)
+// before the split -- exact in fp32 -- and the partial sums are multiplied by the inverse
+// power when they are stored, also exact.  The product then depends on the weights only:
+// with |m| < 16 it stays inside the fp16 range for group scales up to 4094, and the second
+// term (an fp16 denormal as a rule, absolute step 6e-8) carries m * scale to about 2^-21 of
+// the row's largest product whatever the magnitude of the activations.  The right operand
+// holds the codes q + 8 in [0, 15], exact in fp16.  Sums are fp32; the offset leaves as
+// -8 * sum_u m*scale, which a product with an all-ones right operand supplies.
 //
 // Lane l of a wavefront: k-block r = l / 16 (listed columns 4r .. 4r+3 of the 16), c = l % 16.
 // Right operand: the lane loads one dword = 8 codes of each of its 4 stored rows at byte 4c of
@@ -345,6 +365,17 @@ __device__ __forceinline__ h4_t pack_h4(float a, float b, float c, float d) {
     struct { decltype(__builtin_amdgcn_cvt_pkrtz(0.f, 0.f)) lo, hi; } v = {__builtin_amdgcn_cvt_pkrtz(a, b),
                                                                          __builtin_amdgcn_cvt_pkrtz(c, d)};
     return __builtin_bit_cast(h4_t, v);
+}
+
+// The power of two that brings a row's largest |multiplier| (given as its bit pattern) into
+// [8, 16); 1 for an all-zero row.  Denormal and near-overflow maxima are clamped to factors
+// fp32 can hold; such rows only lose the part of the range fp16 could not carry anyway.
+__device__ __forceinline__ float row_scale_up(uint32_t max_bits) {
+    const int e = (int)((max_bits >> 23) & 0xffu);       // biased exponent of the maximum
+    if (max_bits == 0u) return 1.0f;
+    int up = 127 + 3 - (e - 127);                        // biased exponent of 2^(3 - unbiased e)
+    up = up < 1 ? 1 : (up > 254 ? 254 : up);
+    return __uint_as_float((uint32_t)up << 23);
 }
 
 __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemvParams p) {
@@ -388,6 +419,7 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
     const uint32_t row_stride = (uint32_t)p.row_stride;
     const uint32_t wcol[kMGroups] = {(uint32_t)(grp[0] * 64 + 4 * c), (uint32_t)(grp[1] * 64 + 4 * c)};
     const uint32_t cb = (uint32_t)min(c, B - 1);
+    const float row_up = row_scale_up(p.rowmax[cb]);     // this lane's batch row, into [8, 16)
     int4 rn = load_idx(kb + wave * kMRowSet);
     for (int t0 = kb + wave * kMRowSet; t0 < ke; t0 += STEP) {
         const int rows[4] = {rn.x, rn.y, rn.z, rn.w};
@@ -404,7 +436,7 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
             // entries past the share hold whatever the list memory held: they are masked out
             // of the left operand bit-wise (never multiplied away), and the mask is plain
             // arithmetic so that the load stays unconditional
-            mv[i] = p.uval[(uint32_t)min(u, p.k_max - 1) * (uint32_t)B + cb];
+            mv[i] = p.uval[(uint32_t)min(u, p.k_max - 1) * (uint32_t)B + cb] * row_up;
             if (live && row_live) keep[i >> 1] |= (i & 1) ? 0xffff0000u : 0x0000ffffu;
             const uint32_t wrow = rr * row_stride;
             const uint32_t srow = rr * (uint32_t)p.scale_stride;
@@ -489,7 +521,8 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
         const int gcol = strip * kMStripCols + cc;
         if (gcol >= p.n_out) continue;
         const int gg = cc >> 7, cl = (cc & 127) >> 3, t = cc & 7;
-        p.partial[((size_t)g * B + b) * (size_t)p.n_out + gcol] = fmaf(-8.0f, red1[gg][b], red[gg][t][b][cl]);
+        const float row_down = 1.0f / row_scale_up(p.rowmax[b]);     // a power of two: exact
+        p.partial[((size_t)g * B + b) * (size_t)p.n_out + gcol] = fmaf(-8.0f, red1[gg][b], red[gg][t][b][cl]) * row_down;
     }
 }
 
@@ -537,22 +570,23 @@ hipError_t launch_dt(const BatchedGemvParams& p, dim3 grid, hipStream_t stream, 
 
 }  // namespace
 
-bool batched_on_matrix_cores(int dtype, int batch) {
-    return dtype == DIP_INT4_G128 && batch >= kMfmaMinBatch;
+bool batched_on_matrix_cores(int dtype, int batch, int64_t n_in, int64_t row_stride) {
+    // the matrix-core kernel addresses the stored matrix with 32-bit byte offsets
+    return dtype == DIP_INT4_G128 && batch >= kMfmaMinBatch && n_in * row_stride < ((int64_t)1 << 32);
 }
 
-int batched_strip_cols(int dtype, int batch) {
-    if (batched_on_matrix_cores(dtype, batch)) return kMStripCols;
+int batched_strip_cols(int dtype, int batch, bool mc) {
+    if (mc) return kMStripCols;
+    (void)batch;
     return dtype == DIP_F32 ? 16 * 4 : (dtype == DIP_BF16 ? 16 * 8 : 32 * 16);
 }
 
-int batched_shares(int dtype, int batch, int n_out, int k_max) {
+int batched_shares(int dtype, int batch, int n_out, int k_max, bool mc) {
     // Vector-ALU product: about 1024 workgroups, at least 32 listed columns each.
     // Matrix-core product: one round of workgroups -- three of them fit a compute unit, 768
     // in all; 840 take as long as 1536 -- and at least one set of 16 per wavefront.
-    const int sc = batched_strip_cols(dtype, batch);
+    const int sc = batched_strip_cols(dtype, batch, mc);
     const int strips = (n_out + sc - 1) / sc;
-    const bool mc = batched_on_matrix_cores(dtype, batch);
     const int min_rows = mc ? kMWaves * kMRowSet : 32;
     int g = mc ? 768 / strips : (1024 + strips - 1) / strips;
     while (g > 1 && k_max / g < min_rows) --g;
@@ -566,11 +600,14 @@ hipError_t launch_union(const UnionParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int pk) {
-    const int sc = batched_strip_cols(p.dtype, p.batch);
+hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, bool mc, hipStream_t stream, int pk) {
+    const int sc = batched_strip_cols(p.dtype, p.batch, mc);
     dim3 grid((p.n_out + sc - 1) / sc, shares);
-    if (batched_on_matrix_cores(p.dtype, p.batch))
+    if (mc) {
+        if (!p.rowmax || p.dtype != DIP_INT4_G128 || (int64_t)p.n_in * p.row_stride >= ((int64_t)1 << 32))
+            return hipErrorInvalidValue;
         return launch_timed(bgemv_q4_mfma_kernel, grid, dim3(kMWaves * 64), stream, pk, p);
+    }
     if (p.dtype == DIP_F32) return launch_dt<DIP_F32>(p, grid, stream, pk);
     if (p.dtype == DIP_BF16) return launch_dt<DIP_BF16>(p, grid, stream, pk);
     if (p.dtype == DIP_INT4_G128) return launch_dt<DIP_INT4_G128>(p, grid, stream, pk);

@@ -15,7 +15,7 @@
 // strip through a partial buffer that the last workgroup to arrive adds in index order.
 // The result is bit-repeatable for a given launch shape.
 
-#include "dip_internal.h"
+#include "dip_gemv_device.h"
 
 namespace dip {
 
@@ -24,373 +24,21 @@ constexpr int kComputeUnits = 256;   // MI355X
 
 namespace {
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-template <typename WT>
-struct Elem;
-struct q4_t {};  // tag: signed 4-bit codes, one fp16 scale per 128 consecutive elements of a row
-
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-template <>
-struct Elem<float> {
-    typedef u32x4 raw_t;
-    static constexpr int kPerLoad = 4;
-    static constexpr int kBits = 32;
-    static constexpr bool kScaled = false;
-    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[4]) {
-        f[0] = __uint_as_float(q.x);
-        f[1] = __uint_as_float(q.y);
-        f[2] = __uint_as_float(q.z);
-        f[3] = __uint_as_float(q.w);
-    }
-};
-template <>
-struct Elem<uint16_t> {  // bfloat16: the upper half of an fp32 pattern
-    typedef u32x4 raw_t;
-    static constexpr int kPerLoad = 8;
-    static constexpr int kBits = 16;
-    static constexpr bool kScaled = false;
-    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[8]) {
-        f[0] = __uint_as_float(q.x << 16);
-        f[1] = __uint_as_float(q.x & 0xffff0000u);
-        f[2] = __uint_as_float(q.y << 16);
-        f[3] = __uint_as_float(q.y & 0xffff0000u);
-        f[4] = __uint_as_float(q.z << 16);
-        f[5] = __uint_as_float(q.z & 0xffff0000u);
-        f[6] = __uint_as_float(q.w << 16);
-        f[7] = __uint_as_float(q.w & 0xffff0000u);
-    }
-};
-
-template <>
-struct Elem<q4_t> {
-    // 32 codes per 16-byte load, low nibble = even element.  Flipping bit 3 of every nibble
-    // turns the two's-complement code q into q + 8 in [0, 15]; masking even and odd nibbles
-    // apart leaves them as bytes, which convert to float in one instruction each.  The
-    // caller removes the offset: sum (q + 8) m - 8 sum m.
-    typedef u32x4 raw_t;
-    static constexpr int kPerLoad = 32;
-    static constexpr int kBits = 4;
-    static constexpr bool kScaled = true;
-    __device__ static __forceinline__ void widen(const u32x4& q, float (&f)[32]) {
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t o = w[i] ^ 0x88888888u;
-            uint32_t ev = o & 0x0f0f0f0fu, od = (o >> 4) & 0x0f0f0f0fu;
-            // keep the compiler from narrowing the byte extracts below into bit-field
-            // extracts: a byte of a register converts to float in one instruction
-            asm volatile("" : "+v"(ev), "+v"(od));
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                f[i * 8 + 2 * b] = (float)((ev >> (8 * b)) & 0xffu);
-                f[i * 8 + 2 * b + 1] = (float)((od >> (8 * b)) & 0xffu);
-            }
-        }
-    }
-};
-
-struct q4n_t {};  // tag: the same 4-bit format read 8 bytes (16 codes) per lane
-template <>
-struct Elem<q4n_t> {
-    // The column-gathered product keeps one accumulator per code and output segment in
-    // registers; with 32 codes per lane that is 64 accumulators and 163 registers, one
-    // workgroup per compute unit, and every latency of a workgroup's prologue and reduction
-    // is exposed (about 8 us per workgroup).  Half the codes per lane halve the
-    // accumulators, and two to three workgroups share a compute unit.
-    typedef u32x2 raw_t;
-    static constexpr int kPerLoad = 16;
-    static constexpr int kBits = 4;
-    static constexpr bool kScaled = true;
-    __device__ static __forceinline__ void widen(const u32x2& q, float (&f)[16]) {
-        const uint32_t w[2] = {q.x, q.y};
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t o = w[i] ^ 0x88888888u;
-            uint32_t ev = o & 0x0f0f0f0fu, od = (o >> 4) & 0x0f0f0f0fu;
-            asm volatile("" : "+v"(ev), "+v"(od));
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                f[i * 8 + 2 * b] = (float)((ev >> (8 * b)) & 0xffu);
-                f[i * 8 + 2 * b + 1] = (float)((od >> (8 * b)) & 0xffu);
-            }
-        }
-    }
-};
-
-__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
-    _Float16 v;
-    __builtin_memcpy(&v, &h, 2);
-    return (float)v;
-}
-
-__device__ __forceinline__ u32x4 load16(const char* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-}
-template <typename RAW>
-__device__ __forceinline__ RAW load_raw(const char* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const RAW*>(p));
-}
-
-__device__ __forceinline__ float silu(float g) { return g / (1.0f + expf(-g)); }
+using namespace gemv;
 
 template <typename WT, int LPR, int WAVES, int UNROLL, int NSEG>
 __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(GemvParams p) {
-    constexpr int EPL = Elem<WT>::kPerLoad;
-    constexpr int RPW = 64 / LPR;          // rows per wavefront step
-    constexpr int SC = LPR * EPL;          // strip columns
-    __shared__ float red[WAVES][NSEG][SC];
+    typedef Tile<WT, LPR, WAVES, UNROLL, NSEG> T;
+    __shared__ float red[WAVES][NSEG][T::SC];
     __shared__ int s_last;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = lane / LPR, l = lane % LPR;
     const int strip = blockIdx.x;
     const int g = blockIdx.y, G = gridDim.y;
-    const int col_raw = strip * SC + l * EPL;
-    const bool col_ok = col_raw < p.n_out;
-    // lanes past the right edge of a ragged last strip re-read its last 16 bytes; they own no output
-    const int col = col_ok ? col_raw : p.n_out - EPL;
-
     // this workgroup's share of the selected rows
     const int kb = min(p.k, g * p.rows_per_split);   // rows_per_split is a multiple of 8
     const int ke = min(p.k, kb + p.rows_per_split);
-
-    float acc[NSEG][EPL];
-    float msum[NSEG];   // quantised rows: sum of the row multipliers, for the code offset
-#pragma unroll
-    for (int s = 0; s < NSEG; ++s) {
-        msum[s] = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[s][e] = 0.f;
-    }
-
-    const char* wbase = static_cast<const char*>(p.w) + (size_t)col * Elem<WT>::kBits / 8;
-    const char* abase = p.w_alt ? static_cast<const char*>(p.w_alt) + (size_t)col * Elem<WT>::kBits / 8 : wbase;
-    const size_t seg_bytes = (size_t)p.n_out * Elem<WT>::kBits / 8;
-    // quantised rows: the scale of this lane's 32 codes (all inside one group of 128)
-    const int sgroup = col >> 7, sgroups_per_seg = p.n_out >> 7;
-    constexpr int NG = WAVES * RPW;            // lane groups per workgroup
-    constexpr int ROWS_PER_ITER = UNROLL * NG;
-
-    // Every lane group takes UNROLL consecutive selected rows per iteration, so their
-    // indices and multipliers arrive as one vector load each.  Full iterations need no
-    // predicates; the pairs of the next iteration are requested right after this
-    // iteration's weight loads so that their latency hides behind the weights.
-    const int gid = wave * RPW + sub;
-    const int n_full = (ke - kb) / ROWS_PER_ITER;   // the same for every lane
-    const bool ident = p.idx == nullptr;       // every stored row in order (a dense product)
-    int t0 = kb + gid * UNROLL;
-
-    auto fetch_pairs = [&](int t, int (&row)[UNROLL], float (&xv)[UNROLL]) {
-        if constexpr (UNROLL % 4 == 0) {
-#pragma unroll
-            for (int u = 0; u < UNROLL; u += 4) {
-                const float4 x4 = *reinterpret_cast<const float4*>(p.val + t + u);
-                int4 r4 = make_int4(t + u, t + u + 1, t + u + 2, t + u + 3);
-                if (!ident) r4 = *reinterpret_cast<const int4*>(p.idx + t + u);
-                row[u] = r4.x; row[u + 1] = r4.y; row[u + 2] = r4.z; row[u + 3] = r4.w;
-                xv[u] = x4.x; xv[u + 1] = x4.y; xv[u + 2] = x4.z; xv[u + 3] = x4.w;
-            }
-        } else if constexpr (UNROLL == 2) {
-            const float2 x2 = *reinterpret_cast<const float2*>(p.val + t);
-            int2 r2 = make_int2(t, t + 1);
-            if (!ident) r2 = *reinterpret_cast<const int2*>(p.idx + t);
-            row[0] = r2.x; row[1] = r2.y;
-            xv[0] = x2.x; xv[1] = x2.y;
-        } else {
-            xv[0] = p.val[t];
-            row[0] = t;
-            if (!ident) row[0] = p.idx[t];
-        }
-    };
-    // A list entry r >= 0 is stored row r of p.w; an entry r < 0 is stored row ~r of the second
-    // matrix p.w_alt (two-tier residency: the copy of the full matrix in host memory).  An
-    // entry outside its matrix reads row 0 with multiplier 0.
-    auto settle_pairs = [&](int (&row)[UNROLL], float (&xv)[UNROLL], uint32_t& alt) {
-        alt = 0u;
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const bool second = row[u] < 0;
-            const int r = second ? ~row[u] : row[u];
-            const bool inside = (unsigned)r < (unsigned)(second ? p.n_alt : p.n_in);
-            row[u] = inside ? r : 0;
-            xv[u] = inside ? xv[u] : 0.f;
-            alt |= (inside && second) ? (1u << u) : 0u;
-        }
-    };
-    int row[UNROLL];
-    float xv[UNROLL];
-    uint32_t alt = 0u;
-    auto fetch_full = [&](int t) { fetch_pairs(t, row, xv); settle_pairs(row, xv, alt); };
-
-    if (n_full > 0) fetch_full(t0);
-    for (int it = 0; it < n_full; ++it) {
-        typename Elem<WT>::raw_t q[UNROLL][NSEG];
-        uint16_t sc[UNROLL][NSEG];
-        float xc[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const size_t off = (size_t)row[u] * (size_t)p.row_stride;
-            const char* src = ((alt >> u) & 1u) ? abase : wbase;
-            xc[u] = xv[u];
-#pragma unroll
-            for (int s = 0; s < NSEG; ++s) {
-                q[u][s] = load_raw<typename Elem<WT>::raw_t>(src + off + s * seg_bytes);
-                if constexpr (Elem<WT>::kScaled)
-                    sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
-            }
-        }
-        t0 += ROWS_PER_ITER;
-        if (it + 1 < n_full) fetch_full(t0);
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-#pragma unroll
-            for (int s = 0; s < NSEG; ++s) {
-                float f[EPL];
-                Elem<WT>::widen(q[u][s], f);
-                float mult = xc[u];
-                if constexpr (Elem<WT>::kScaled) {
-                    mult *= half_bits_to_float(sc[u][s]);
-                    msum[s] += mult;
-                }
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
-            }
-        }
-    }
-    // Tail: fewer than ROWS_PER_ITER rows are left; rows past the end are skipped.
-    if (col_ok && t0 < ke) {
-        typename Elem<WT>::raw_t q[UNROLL][NSEG];
-        uint16_t sc[UNROLL][NSEG];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int t = t0 + u;
-            row[u] = -1;
-            xv[u] = 0.f;
-            if (t < ke) {
-                const int e = ident ? t : p.idx[t];
-                const bool second = e < 0;
-                const int r = second ? ~e : e;
-                if ((unsigned)r < (unsigned)(second ? p.n_alt : p.n_in)) {
-                    row[u] = r;
-                    xv[u] = p.val[t];
-                    alt = second ? (alt | (1u << u)) : (alt & ~(1u << u));
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-#pragma unroll
-            for (int s = 0; s < NSEG; ++s) {
-                q[u][s] = typename Elem<WT>::raw_t{};
-                sc[u][s] = 0;
-                if (row[u] >= 0) {
-                    const char* src = ((alt >> u) & 1u) ? abase : wbase;
-                    q[u][s] = load_raw<typename Elem<WT>::raw_t>(src + (size_t)row[u] * (size_t)p.row_stride + s * seg_bytes);
-                    if constexpr (Elem<WT>::kScaled)
-                        sc[u][s] = p.scales[(size_t)row[u] * p.scale_stride + s * sgroups_per_seg + sgroup];
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-#pragma unroll
-            for (int s = 0; s < NSEG; ++s) {
-                float f[EPL];
-                Elem<WT>::widen(q[u][s], f);
-                float mult = xv[u];
-                if constexpr (Elem<WT>::kScaled) {
-                    mult *= half_bits_to_float(sc[u][s]);
-                    msum[s] += mult;
-                }
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(f[e], mult, acc[s][e]);
-            }
-        }
-    }
-
-    if constexpr (Elem<WT>::kScaled) {
-#pragma unroll
-        for (int s = 0; s < NSEG; ++s)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[s][e] = fmaf(-8.0f, msum[s], acc[s][e]);
-    }
-
-    // lane groups of one wavefront
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-#pragma unroll
-        for (int s = 0; s < NSEG; ++s)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[s][e] += __shfl_xor(acc[s][e], off);
-    }
-    if (sub == 0) {
-#pragma unroll
-        for (int s = 0; s < NSEG; ++s)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) red[wave][s][l * EPL + e] = acc[s][e];
-    }
-    __syncthreads();
-
-    // wavefronts of one workgroup: lane c of the first NSEG*SC lanes owns one output
-    constexpr int NOUT = NSEG * SC;
-    static_assert(NOUT <= WAVES * 64, "strip wider than the workgroup");  // launch_nseg guards this
-    const int oseg = tid / SC, ocol = tid % SC;
-    const int gcol = strip * SC + ocol;
-    const bool owner = tid < NOUT && gcol < p.n_out;
-    float sum = 0.f;
-    if (owner) {
-#pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[w][oseg][ocol];
-    }
-
-    if (G > 1) {
-        // Workgroups of one strip.  Partial sums travel through agent-scope atomics, which
-        // are written through to (and read from) the memory side where all eight L2s agree,
-        // so no L2 write-back or invalidate is needed: waiting for the stores to be
-        // acknowledged (vmcnt = 0) before this workgroup's ticket is taken orders them
-        // before any read by the workgroup that draws the last ticket.
-        float* part = p.partial + ((size_t)g * NSEG + oseg) * (size_t)p.n_out + gcol;
-        if (owner) __hip_atomic_store(part, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) {
-            const uint32_t prev = __hip_atomic_fetch_add(&p.counters[strip], 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            s_last = (prev == (uint32_t)(G - 1));
-        }
-        __syncthreads();
-        if (!s_last) return;
-        // eight partial sums in flight at a time, added in workgroup order
-        sum = 0.f;
-        if (owner) {
-            const float* src0 = p.partial + (size_t)oseg * (size_t)p.n_out + gcol;
-            const size_t gstride = (size_t)NSEG * (size_t)p.n_out;
-            for (int g0 = 0; g0 < G; g0 += 8) {
-                float part8[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int gg = g0 + j < G ? g0 + j : G - 1;
-                    part8[j] = __hip_atomic_load(src0 + (size_t)gg * gstride, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (g0 + j < G) sum += part8[j];
-            }
-        }
-    }
-
-    if constexpr (NSEG == 2) {
-        // Sec. 3 Eq. 2: GLU = up (.) SiLU(gate); the gate sums sit SC lanes further on
-        __syncthreads();
-        if (owner) red[0][oseg][ocol] = sum;
-        __syncthreads();
-        if (owner && oseg == 0) p.out[gcol] = red[0][0][ocol] * silu(red[0][1][ocol]);
-    } else {
-        if (owner) p.out[gcol] = p.act == 1 ? silu(sum) : sum;
-    }
+    float acc[NSEG][T::EPL];
+    accumulate<WT, LPR, WAVES, UNROLL, NSEG>(p, p.idx, p.val, 0, kb, ke, strip, acc);
+    finish<WT, LPR, WAVES, UNROLL, NSEG, true>(p, acc, strip, g, G, red, s_last);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -703,6 +351,66 @@ GemvShape choose_gemv_shape(int dtype, int n_out, int nseg, int k) {
     return s;
 }
 
+int g_fusion = 1;
+
+// Launch shape of a product that runs its own selection: 16 wavefronts per workgroup, one
+// workgroup per compute unit (every workgroup repeats the selection, so a second round would
+// pay it twice), hence strips * ksplit as close to the 256 compute units as the strip widths
+// allow, every share at least one full iteration of rows and at most the LDS list.
+bool fused_shape(int dtype, int n_sel, int n_out, int nseg, int k, GemvShape* shape) {
+    if (!g_fusion) return false;
+    if (n_sel > DIP_MAX_N || (nseg == 2 && n_sel > kFusedMaxIn)) return false;
+    const int epl = elems_per_load(dtype);
+    GemvShape best = {0, 16, 0, 4};
+    int best_wgs = 0;
+    const int lprs[3] = {32, 64, 16};
+    for (int li = 0; li < 3; ++li) {
+        const int lpr = lprs[li];
+        if (g_gemv_override.lpr && g_gemv_override.lpr != lpr) continue;
+        if (nseg * lpr * epl > kSelThreads) continue;        // a strip's outputs, one lane each
+        const int strips = (n_out + lpr * epl - 1) / (lpr * epl);
+        const int rows_per_iter = 4 * 16 * (64 / lpr);
+        int ks = kComputeUnits / strips;
+        if (ks > k / rows_per_iter) ks = k / rows_per_iter;
+        if (ks < 1) ks = 1;
+        if (g_gemv_override.ksplit) ks = g_gemv_override.ksplit;
+        if (ks > k) ks = k;
+        const int share = ((k + ks - 1) / ks + 7) / 8 * 8;
+        if (share > kFusedListCap) continue;
+        int wgs = strips * ks;
+        if (wgs > kComputeUnits) wgs = kComputeUnits - 1;    // more than one round: last choice
+        if (wgs > best_wgs) {
+            best_wgs = wgs;
+            best.lpr = lpr;
+            best.ksplit = ks;
+        }
+    }
+    if (!best_wgs) return false;
+    *shape = best;
+    return true;
+}
+
+hipError_t launch_fused(const FusedParams& p0, const GemvShape& s, hipStream_t stream, int pk) {
+    FusedParams p = p0;
+    p.g.rows_per_split = ((p.g.k + s.ksplit - 1) / s.ksplit + 7) / 8 * 8;
+    if (p.g.rows_per_split > kFusedListCap || s.waves != 16 || s.unroll != 4) return hipErrorInvalidConfiguration;
+    if (p.s.n < 1 || p.s.n > DIP_MAX_N || p.g.k < 1 || p.g.k > p.s.n || p.s.n != p.g.n_in) return hipErrorInvalidValue;
+    p.g.idx = nullptr;
+    p.g.val = nullptr;
+    p.g.w_alt = nullptr;
+    p.g.n_alt = 0;
+    if (p.g.nseg == 2) {
+        if (p.g.dtype == DIP_F32) return launch_fused_2_0(p, s, stream, pk);
+        if (p.g.dtype == DIP_BF16) return launch_fused_2_1(p, s, stream, pk);
+        if (p.g.dtype == DIP_INT4_G128) return launch_fused_2_2(p, s, stream, pk);
+    } else {
+        if (p.g.dtype == DIP_F32) return launch_fused_1_0(p, s, stream, pk);
+        if (p.g.dtype == DIP_BF16) return launch_fused_1_1(p, s, stream, pk);
+        if (p.g.dtype == DIP_INT4_G128) return launch_fused_1_2(p, s, stream, pk);
+    }
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_gemv(const GemvParams& p0, const GemvShape& s, hipStream_t stream, int pk) {
     GemvParams p = p0;
     p.rows_per_split = ((p.k + s.ksplit - 1) / s.ksplit + 7) / 8 * 8;   // keeps vector index loads aligned
@@ -723,6 +431,39 @@ __global__ void gather_kernel(const float* x, const int32_t* idx, int k, int n, 
 hipError_t launch_gather(const float* x, const int32_t* idx, int k, int n, float* val, int32_t* idx_copy,
                          hipStream_t stream) {
     hipLaunchKernelGGL(gather_kernel, dim3((k + 255) / 256), dim3(256), 0, stream, x, idx, k, n, val, idx_copy);
+    return hipGetLastError();
+}
+
+// A plain streaming read of `bytes` bytes (whole 16-byte pieces), for benchmarks: what the
+// memory system delivers to a kernel that does nothing but load, in the same run and on the
+// same box as the gathered products it is compared with.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, size_t n16, uint32_t* sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) q[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= q[u];
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    // (never true for the buffers benchmarks use; keeps the loads alive)
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
+}
+
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream, int prof_kind) {
+    const size_t n16 = bytes / 16;
+    struct Args { const u32x4* src; size_t n16; uint32_t* sink; };
+    hipEvent_t e0, e1;
+    const dim3 grid(kComputeUnits * 16), block(256);
+    if (prof_kind >= 0 && prof_next(prof_kind, &e0, &e1)) {
+        hipExtLaunchKernelGGL(stream_read_kernel, grid, block, 0, stream, e0, e1, 0,
+                              static_cast<const u32x4*>(src), n16, sink);
+    } else {
+        hipLaunchKernelGGL(stream_read_kernel, grid, block, 0, stream, static_cast<const u32x4*>(src), n16, sink);
+    }
     return hipGetLastError();
 }
 

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "dip.h"
+#include "dip_devtools.h"
 
 namespace dip {
 
@@ -39,7 +40,7 @@ struct SelectParams {
     const float* v;               // input vector (x or h~), n floats
     int n;
     int k;
-    const uint32_t* score_bits;   // residency used for scoring (Eq. 6), or null for |v|
+    const uint32_t* score_bits;   // residency used for scoring (Eq. 10), or null for |v|
     float gamma;
     const uint32_t* mask_in;      // non-null: take the mask from here instead of selecting
     int scores_only;              // 1: write s_out and return
@@ -69,6 +70,20 @@ struct SelectParams {
 // `second`, `third`: independent single-row work for further workgroups of the same launch
 hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind,
                          const SelectParams* second = nullptr, const SelectParams* third = nullptr);
+
+// Cache updates of several caches in one launch, one workgroup each (nothing in the token
+// that produced the masks waits for them).
+struct UpdatePiece {
+    const uint32_t* mask;         // this token's mask words
+    uint32_t* bits;
+    uint32_t* stamp;
+    uint32_t* meta;
+    int n;
+    int capacity;
+    int policy;
+    int pad;
+};
+hipError_t launch_update_batch(const UpdatePiece* pieces, int count, hipStream_t stream, int prof_kind);
 
 struct CacheInitParams {
     uint32_t* bits;
@@ -137,6 +152,36 @@ hipError_t launch_gather(const float* x, const int32_t* idx, int k, int n, float
                          hipStream_t stream);
 
 extern GemvShape g_gemv_override;
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream, int prof_kind);
+
+// ---- gathered product with the selection at its head (one launch for Alg. 1 steps 1, 2, 4) ----
+constexpr int kFusedListCap = 2048;   // rows of one workgroup's share (index + multiplier in LDS)
+constexpr int kFusedMaxIn = 8192;     // longest input vector of the bundled up/gate product
+struct FusedSelect {
+    const float* v;               // the vector the mask is taken from (x or h~), n floats
+    int n;
+    const uint32_t* score_bits;   // residency for Eq. 10 scores, or null for |v|
+    float gamma;
+    // launch-wide outputs, written by one workgroup (mask, scores) or the workgroups of strip 0
+    // (index list); each may be null
+    uint32_t* mask_out;
+    int32_t* idx_out;
+    float* s_out;
+};
+struct FusedParams {
+    GemvParams g;                 // idx / val are ignored: the lists live in LDS
+    FusedSelect s;
+};
+// false when no kernel covers the shape (then the caller launches selection and product apart)
+bool fused_shape(int dtype, int n_sel, int n_out, int nseg, int k, GemvShape* shape);
+hipError_t launch_fused(const FusedParams& p, const GemvShape& s, hipStream_t stream, int prof_kind);
+hipError_t launch_fused_1_0(const FusedParams&, const GemvShape&, hipStream_t, int);
+hipError_t launch_fused_1_1(const FusedParams&, const GemvShape&, hipStream_t, int);
+hipError_t launch_fused_1_2(const FusedParams&, const GemvShape&, hipStream_t, int);
+hipError_t launch_fused_2_0(const FusedParams&, const GemvShape&, hipStream_t, int);
+hipError_t launch_fused_2_1(const FusedParams&, const GemvShape&, hipStream_t, int);
+hipError_t launch_fused_2_2(const FusedParams&, const GemvShape&, hipStream_t, int);
+extern int g_fusion;              // 0: always launch selection and product apart
 
 // ---- small batches: union of row masks, batched gathered product, reduction ------------------
 struct UnionParams {
@@ -150,6 +195,7 @@ struct UnionParams {
     int32_t* uidx;             // ascending indices of the union, up to min(n, batch*k)
     float* uval;               // [listed][batch]: x[b][i] if row b selected i, else 0
     uint32_t* count_out;       // number of listed indices
+    uint32_t* rowmax;          // [batch], zero on entry: bit pattern of the largest |x[b][i]| listed for row b; nullable
 };
 struct BatchedGemvParams {
     const void* w;
@@ -165,6 +211,7 @@ struct BatchedGemvParams {
     int k_max;                 // capacity of the lists
     int batch;
     float* partial;            // [shares][batch][n_out]
+    const uint32_t* rowmax;    // [batch] from the union kernel (matrix-core product only)
 };
 struct BatchedReduceParams {
     const float* partial;
@@ -175,11 +222,11 @@ struct BatchedReduceParams {
     float* out;
     int64_t out_stride;
 };
-bool batched_on_matrix_cores(int dtype, int batch);
-int batched_strip_cols(int dtype, int batch);
-int batched_shares(int dtype, int batch, int n_out, int k_max);
+bool batched_on_matrix_cores(int dtype, int batch, int64_t n_in, int64_t row_stride);
+int batched_strip_cols(int dtype, int batch, bool mc);
+int batched_shares(int dtype, int batch, int n_out, int k_max, bool mc);
 hipError_t launch_union(const UnionParams& p, hipStream_t stream);
-hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, hipStream_t stream, int prof_kind);
+hipError_t launch_batched_gemv(const BatchedGemvParams& p, int shares, bool mc, hipStream_t stream, int prof_kind);
 hipError_t launch_batched_reduce(const BatchedReduceParams& p, hipStream_t stream);
 
 // ---- two-tier residency: slot map of the HBM cache, fill list, encoded row list -----------------

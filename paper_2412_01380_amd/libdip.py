@@ -109,9 +109,11 @@ def _load() -> C.CDLL:
     L.dip_swiglu_mlp_forward_noalloc.argtypes = [C.POINTER(_Mlp), vp, i32, i32, C.POINTER(_Cache),
                                                  C.POINTER(_Cache), f32, vp, C.POINTER(_Debug), vp]
     L.dip_swiglu_mlp_forward_stack.restype = i32
-    L.dip_swiglu_mlp_forward_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, i32, i32,
+    L.dip_swiglu_mlp_forward_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, C.POINTER(i32), C.POINTER(i32),
                                                C.POINTER(_Cache), C.POINTER(_Cache), f32, vp, i64,
                                                vp, sz, vp]
+    L.dip_swiglu_mlp_forward_stack_workspace_bytes.restype = sz
+    L.dip_swiglu_mlp_forward_stack_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32, C.POINTER(i32), C.POINTER(i32)]
     L.dip_swiglu_mlp_forward_batched_workspace_bytes.restype = sz
     L.dip_swiglu_mlp_forward_batched_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32, i32, i32]
     L.dip_swiglu_mlp_forward_batched.restype = i32
@@ -141,6 +143,12 @@ def _load() -> C.CDLL:
     L.dip_tune_gemv.argtypes = [i32, i32, i32, i32]
     L.dip_gemv_launch_shape.restype = i32
     L.dip_gemv_launch_shape.argtypes = [C.POINTER(_Weight), i32, i32, C.POINTER(i32)]
+    L.dip_set_fusion.restype = i32
+    L.dip_set_fusion.argtypes = [i32]
+    L.dip_fused_launch_shape.restype = i32
+    L.dip_fused_launch_shape.argtypes = [C.POINTER(_Weight), i32, i32, C.POINTER(i32)]
+    L.dip_stream_read.restype = i32
+    L.dip_stream_read.argtypes = [vp, sz, vp, vp]
     L.dip_profile_enable.restype = i32
     L.dip_profile_enable.argtypes = [i32]
     L.dip_profile_read.restype = i32
@@ -156,11 +164,12 @@ EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "
            "dip_cache_update", "dip_cache_state_bytes", "dip_cache_blob_bytes", "dip_cache_export",
            "dip_cache_import", "dip_gathered_gemv_workspace_bytes", "dip_gathered_gemv",
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
-           "dip_swiglu_mlp_forward_noalloc", "dip_swiglu_mlp_forward_stack", "dip_swiglu_mlp_forward_batched_workspace_bytes",
+           "dip_swiglu_mlp_forward_noalloc", "dip_swiglu_mlp_forward_stack",
+           "dip_swiglu_mlp_forward_stack_workspace_bytes", "dip_swiglu_mlp_forward_batched_workspace_bytes",
            "dip_swiglu_mlp_forward_batched", "dip_glu_pruning_forward_workspace_bytes",
            "dip_glu_pruning_forward", "dip_gathered_rowdot",
            "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tier_init_workspace_bytes",
-           "dip_tier_init", "dip_tiered_mlp_forward_workspace_bytes", "dip_tiered_mlp_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_profile_enable", "dip_profile_read",
+           "dip_tier_init", "dip_tiered_mlp_forward_workspace_bytes", "dip_tiered_mlp_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_set_fusion", "dip_fused_launch_shape", "dip_stream_read", "dip_profile_enable", "dip_profile_read",
            "dip_profile_disable"]
 
 
@@ -439,11 +448,27 @@ class MlpStack:
         self._keep = (list(mlps), caches_in, caches_mid)
 
 
-def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in: int, k_mid: int,
+def _k_array(k, n: int):
+    """One k for all layers, or a sequence of n_layers values -> a host int32 array."""
+    vals = [int(k)] * n if isinstance(k, int) else [int(v) for v in k]
+    if len(vals) != n:
+        raise ValueError(f"expected {n} values of k, got {len(vals)}")
+    return (C.c_int32 * n)(*vals)
+
+
+def dip_swiglu_mlp_forward_stack_workspace_bytes(stack: MlpStack, k_in, k_mid) -> int:
+    return lib.dip_swiglu_mlp_forward_stack_workspace_bytes(stack.mlps, stack.n, _k_array(k_in, stack.n),
+                                                            _k_array(k_mid, stack.n))
+
+
+def dip_swiglu_mlp_forward_stack(stack: MlpStack, x, x_stride: int, k_in, k_mid,
                                  gamma: float, y_out, y_stride: int, ws, stream=None) -> None:
+    """k_in / k_mid: an int for all layers, a sequence of per-layer values, or a ctypes int32 array."""
     import torch
+    ki = k_in if isinstance(k_in, C.Array) else _k_array(k_in, stack.n)
+    km = k_mid if isinstance(k_mid, C.Array) else _k_array(k_mid, stack.n)
     _check(lib.dip_swiglu_mlp_forward_stack(
-        stack.mlps, stack.n, _ptr(x, torch.float32), x_stride, k_in, k_mid, stack.cin, stack.cmid,
+        stack.mlps, stack.n, _ptr(x, torch.float32), x_stride, ki, km, stack.cin, stack.cmid,
         gamma, _ptr(y_out, torch.float32), y_stride, _ptr(ws), ws.numel() * ws.element_size(),
         _stream(stream)))
 
@@ -534,6 +559,26 @@ def dip_gemv_launch_shape(w: Weight, k: int, bundled: bool = False):
     out = (C.c_int32 * 4)()
     _check(lib.dip_gemv_launch_shape(C.byref(w.c), k, 1 if bundled else 0, out))
     return tuple(out)
+
+
+def dip_set_fusion(on: bool) -> None:
+    _check(lib.dip_set_fusion(1 if on else 0))
+
+
+def dip_fused_launch_shape(w: Weight, k: int, bundled: bool = False):
+    """(lanes_per_row, waves, ksplit, unroll) of the one-launch form, or None when the forward
+    calls launch selection and product apart for this shape."""
+    out = (C.c_int32 * 4)()
+    st = lib.dip_fused_launch_shape(C.byref(w.c), k, 1 if bundled else 0, out)
+    if st == DIP_ERR_UNSUPPORTED:
+        return None
+    _check(st)
+    return tuple(out)
+
+
+def dip_stream_read(src, sink, stream=None) -> None:
+    """Plain streaming read of the whole tensor `src` (timed as profile kind 8)."""
+    _check(lib.dip_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
 
 
 def dip_profile_enable(max_launches: int) -> None:

@@ -16,7 +16,7 @@ def D():
 
 
 def header_functions():
-    src = open(os.path.join(ROOT, "include", "dip.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("dip.h", "dip_devtools.h"))
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(dip_[a-z0-9_]+)\s*\(", src)))
 

@@ -8,7 +8,8 @@ import torch
 
 from oracle import dip_oracle as O
 from workloads import CONFIGS, ar1_laplace_stream, layer_weights
-from gpu_util import bits_from_bool, bool_from_bits, dev_f32, host_u32, make_weight, rel_l2, workspace
+from gpu_util import (assert_product_close, bits_from_bool, bool_from_bits, dev_f32, glu_scale, host_u32, make_weight,
+                      rel_l2, workspace)
 
 pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-3, "int4": 2e-3}
@@ -23,6 +24,7 @@ def D():
 def run_steps(D, d, f, fmt, B, k_in, k_mid, steps, use_cache, seed, layer=0, cap_frac=0.5):
     w = layer_weights(d, f, seed=seed, layer=layer, dtype=fmt)
     mlp = D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"]))
+    vector = not (fmt == "int4" and B >= 3)       # that case runs on the matrix cores (own bar)
     ws = workspace(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlp, B, k_in, k_mid))
     wd, wf = (d + 31) // 32, (f + 31) // 32
     m1 = torch.empty(B, wd, dtype=torch.int32, device="cuda")
@@ -49,12 +51,17 @@ def run_steps(D, d, f, fmt, B, k_in, k_mid, steps, use_cache, seed, layer=0, cap
         for b in range(B):
             mb1, idx1 = O.topk(O.score(X[b], c_in, 0.2), k_in)
             assert np.array_equal(host_u32(m1[b]), bits_from_bool(mb1)), (t, b, "mask 1")
-            h_ref = O.glu_from_preacts(O.gathered_gemv(w["ug"], X[b], idx1))
+            pre = O.gathered_gemv(w["ug"], X[b], idx1)
+            h_ref = O.glu_from_preacts(pre)
             assert rel_l2(Hg[b], h_ref) <= TOL[fmt], (t, b, "h")
+            if vector:
+                assert_product_close(Hg[b], h_ref, fmt, k_in, (t, b, "h"), scale=glu_scale(pre), factor=3.0)
             mb2, idx2 = O.topk(O.score(Hg[b], c_mid, 0.2), k_mid)
             assert np.array_equal(host_u32(m2[b]), bits_from_bool(mb2)), (t, b, "mask 2")
             y_ref = O.gathered_gemv(w["d"], Hg[b], idx2)
             assert rel_l2(Yg[b], y_ref) <= TOL[fmt], (t, b, "y")
+            if vector:
+                assert_product_close(Yg[b], y_ref, fmt, k_mid, (t, b, "y"))
             M1.append(mb1)
             M2.append(mb2)
         if use_cache:

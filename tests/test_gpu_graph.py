@@ -45,7 +45,7 @@ def test_stack_forward_replays_from_a_graph(D, fmt, use_cache):
     ce, cg = (_caches(D, L, d, f, 200, 700), _caches(D, L, d, f, 200, 700)) if use_cache else ((None, None),) * 2
     stack_e = D.MlpStack(mlps, ce[0], ce[1])
     stack_g = D.MlpStack(mlps, cg[0], cg[1])
-    nbytes = D.dip_swiglu_mlp_forward_workspace_bytes(mlps[0], k_in, k_mid)
+    nbytes = D.dip_swiglu_mlp_forward_stack_workspace_bytes(stack_e, k_in, k_mid)
     ws_e, ws_g = workspace(nbytes), workspace(nbytes)
     T = 6
     X = dev_f32(ar1_laplace_stream(L * T, d, seed=8).reshape(T, L, d))

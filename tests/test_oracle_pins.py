@@ -60,10 +60,10 @@ def rel_l2(a, b):
 
 
 # --------------------------------------------------------------------------
-# golden: Eq. 6 worked by hand
+# golden: Eq. 10 worked by hand
 # --------------------------------------------------------------------------
-def test_eq6_hand_worked_cases():
-    with open(os.path.join(GOLDEN, "eq6_hand_worked.json")) as fh:
+def test_eq10_hand_worked_cases():
+    with open(os.path.join(GOLDEN, "eq10_hand_worked.json")) as fh:
         cases = json.load(fh)["cases"]
     for c in cases:
         x = np.array(c["x"], dtype=np.float32)
@@ -122,7 +122,7 @@ def test_topk_rejects_bad_k():
 
 
 # --------------------------------------------------------------------------
-# Eq. 6 identities
+# Eq. 10 identities
 # --------------------------------------------------------------------------
 def test_score_plain_dip_key_is_magnitude():
     x = studentt_tokens(1, 257, 3)[0]
@@ -157,7 +157,7 @@ def test_score_scale_invariance_power_of_two():
 
 
 def test_gamma_one_is_plain_dip():
-    """gamma = 1 is the DIP instance (Sec. 6.3): no re-weighting.  With ||x||_inf a power
+    """gamma = 1 is the DIP instance (Sec. 6.4): no re-weighting.  With ||x||_inf a power
     of two the division is exact, so the masks are identical bit for bit."""
     rng = np.random.default_rng(7)
     x = rng.standard_normal(400).astype(np.float32)
@@ -494,7 +494,7 @@ def test_lru_inclusion_property_hit_rate_monotone_in_capacity():
 
 
 def test_lru_bypass_when_active_set_exceeds_cache():
-    """Sec. 6.3: below some sparsity the active set no longer fits; the cache then holds
+    """Sec. 6.4: below some sparsity the active set no longer fits; the cache then holds
     part of the current neurons and the rest is streamed without being cached."""
     st = O.CacheState(n=10, capacity=3)
     m = np.zeros(10, dtype=bool)
@@ -528,6 +528,47 @@ def test_lfu_single_item_trace_matches_counter_dict():
                 res.remove(victim)
             res.add(p)
         assert set(np.flatnonzero(st.resident)) == res
+
+
+def naive_counter_lfu_step(res, counts, cap, mset):
+    """LFU by the book, one column after the other: every use is counted; a missed column takes
+    a free place, else the place of the resident with the smallest (count, index) among those
+    this token does not use; if there is none it is not cached."""
+    for i in sorted(mset):
+        counts[i] += 1
+    for i in sorted(mset):
+        if i in res:
+            continue
+        if len(res) < cap:
+            res.add(i)
+            continue
+        cands = [j for j in res if j not in mset]
+        if not cands:
+            continue
+        res.remove(min(cands, key=lambda j: (counts[j], j)))
+        res.add(i)
+    return res
+
+
+@pytest.mark.parametrize("n,steps", [(4, 3), (3, 5)])
+def test_lfu_set_valued_exhaustive_tiny(n, steps):
+    """Every sequence of masks over n columns, every capacity: several misses and several
+    evictions in one step, with equal use counts among the candidates (index decides)."""
+    all_masks = [ms for r in range(1, n + 1) for ms in itertools.combinations(range(n), r)]
+    for cap in range(0, n + 1):
+        for seq in itertools.product(all_masks, repeat=steps):
+            st = O.CacheState(n=n, capacity=cap, policy="lfu")
+            res, counts = set(), [0] * n
+            for ms in seq:
+                m = np.zeros(n, dtype=bool)
+                m[list(ms)] = True
+                before = st.resident.copy()
+                O.cache_update(st, m)
+                res = naive_counter_lfu_step(res, counts, cap, set(ms))
+                assert set(np.flatnonzero(st.resident)) == res, (cap, seq)
+                assert st.stamp.tolist() == counts, (cap, seq)
+                assert int(st.resident.sum()) <= cap
+                assert np.all(st.resident[m & before])           # a hit is never evicted
 
 
 # --------------------------------------------------------------------------
