@@ -41,6 +41,25 @@ struct HeadShared {
     float wave_max[kWaves];
     uint32_t bcast[4];
 };
+constexpr int kHeadHistWords = kBinsA + kBinsB + kBinsC;
+
+// Exclusive running sums of the per-tile counts over the tiles in index order: lane j of each
+// wavefront passes the count of the wavefront's tile in slot j and gets the sum over the tiles
+// before it; `total` is the sum over all tiles.
+template <int ITEMS>
+__device__ __forceinline__ uint32_t tile_scan(uint32_t cnt, HeadShared& sh, int& phase, uint32_t& total) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ntiles = ITEMS * kWaves;
+    if (lane < ITEMS) sh.tile[0][lane * kWaves + wave] = cnt;
+    __syncthreads();
+    const uint32_t t = tid < ntiles ? sh.tile[0][tid] : 0u;
+    const uint32_t ex = block_excl_scan(t, sh, phase);
+    if (tid < ntiles) sh.tile[0][tid] = ex;
+    if (tid == ntiles - 1) sh.bcast[3] = ex + t;
+    __syncthreads();
+    total = sh.bcast[3];
+    return lane < ITEMS ? sh.tile[0][lane * kWaves + wave] : 0u;
+}
 
 // Smallest float bit pattern c in [lo, hi] with pred(fl(c / M)) true, where pred is monotone
 // (false ... false true ... true) and true at hi.  Every lane runs the same bisection.
@@ -70,6 +89,7 @@ __device__ __forceinline__ uint32_t tile_prefix_window(const uint32_t (&key)[ITE
         const uint32_t cg = (uint32_t)__popcll(__ballot(key[j] >= K_hi));
         mine = lane == j ? (ce | (cg << 16)) : mine;
     }
+    __syncthreads();       // (the table may still be read by a slower wavefront)
     if (lane < ITEMS) sh.tile[0][lane * kWaves + wave] = mine;
     __syncthreads();
     const uint32_t t = tid < ntiles ? sh.tile[0][tid] : 0u;
@@ -80,6 +100,28 @@ __device__ __forceinline__ uint32_t tile_prefix_window(const uint32_t (&key)[ITE
     totals = sh.bcast[3];
     return lane < ITEMS ? sh.tile[0][lane * kWaves + wave] : 0u;
 }
+
+// One slot of the selection `key >= T` into the workgroup's share of the list; slots whose
+// bit of `active` is clear cost one scalar test.  (A template recursion rather than a loop:
+// the lane numbers must be constants.)
+template <int J, int ITEMS>
+struct ListGe {
+    __device__ static __forceinline__ void run(const uint32_t (&key)[ITEMS], const float (&v)[ITEMS], uint32_t T,
+                                               int pre, uint64_t active, int kb, int ke, int32_t* l_idx,
+                                               float* l_val) {
+        if ((active >> J) & 1ull) {     // wave-uniform
+            const bool mine = key[J] >= T;
+            const uint64_t bs = __ballot(mine);
+            const uint32_t at = (uint32_t)__builtin_amdgcn_readlane(pre, J) + lanes_below(bs) - (uint32_t)kb;
+            // (at < ke - kb also rejects the places before kb, which wrap around)
+            if (mine && at < (uint32_t)(ke - kb)) {
+                l_idx[at & (kFusedListCap - 1)] = J * kSelThreads + (int)threadIdx.x;
+                l_val[at & (kFusedListCap - 1)] = v[J];
+            }
+        }
+        if constexpr (J + 1 < ITEMS) ListGe<J + 1, ITEMS>::run(key, v, T, pre, active, kb, ke, l_idx, l_val);
+    }
+};
 
 template <typename WT, int LPR, int NSEG>
 struct FusedShared {
@@ -116,13 +158,24 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
     uint32_t key[ITEMS];
     const int mine_n = q.n > tid ? (q.n - tid - 1) / kSelThreads + 1 : 0;
     const uint32_t valid = mine_n >= 32 ? 0xffffffffu : (1u << mine_n) - 1u;
+    {
+        const float* vp = q.v + tid;
+        const int full = q.n >> 10;     // slots that lie inside the vector entirely (wave-uniform)
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {   // past the end the last element is read and dropped
-        const uint32_t i = (uint32_t)(j * kSelThreads + tid);
-        const float t = q.v[min(i, (uint32_t)q.n - 1u) & (DIP_MAX_N - 1)];
-        v[j] = i < (uint32_t)q.n ? t : 0.f;
+        for (int j = 0; j < ITEMS; ++j) {
+            if (j < full) {
+                v[j] = vp[j * kSelThreads];
+            } else {
+                const uint32_t i = (uint32_t)(j * kSelThreads + tid);
+                v[j] = 0.f;
+                if (i < (uint32_t)q.n) v[j] = q.v[i & (DIP_MAX_N - 1)];
+            }
+        }
     }
-    for (int b = tid; b < kBinsA + kBinsB + kBinsC; b += kSelThreads) hs.hist[b] = 0u;
+    static_assert(kHeadHistWords % (2 * kSelThreads) == 0, "the histograms are cleared in 8-byte pieces");
+#pragma unroll
+    for (int b = 0; b < kHeadHistWords / (2 * kSelThreads); ++b)
+        reinterpret_cast<uint2*>(hs.hist)[b * kSelThreads + tid] = make_uint2(0u, 0u);
     hs.cw[tid] = (q.score_bits && tid < nwords) ? q.score_bits[tid] : 0u;
     __syncthreads();
 
@@ -144,8 +197,8 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
         for (int j = 0; j < ITEMS; ++j) key[j] = __float_as_uint(fabsf(v[j])) << 1;
     }
 
-    uint32_t Tk, need, n_equal;
-    block_select_largest<ITEMS, false>(key, (uint32_t)p.k, hs, phase, Tk, need, true, &n_equal);
+    uint32_t Tk, need;
+    block_select_largest<ITEMS, false>(key, (uint32_t)p.k, hs, phase, Tk, need, true);
 
     // keys in [K_lo, K_hi) tie at the k-th largest score, keys >= K_hi lie above it
     uint32_t K_lo = Tk, K_hi = Tk + 1u;
@@ -179,32 +232,23 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
         }
     }
 
-    const bool list_idx = q.idx_out && strip == 0;   // the workgroups of strip 0 cover all of [0, k)
-    if (K_lo == Tk && K_hi <= Tk + 2u && need == n_equal) {
-        // No tie is split at the threshold (the usual case): the selection is key >= T and a
-        // selected key's place in the list is the number of such keys before it.
-        const int pre = (int)tile_prefix_ge<ITEMS>(key, Tk, hs, phase);
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const bool mine = key[j] >= Tk;
-            const uint64_t bs = __ballot(mine);
-            const uint32_t before = (uint32_t)__builtin_amdgcn_readlane(pre, j);
-            const uint32_t cnt = (uint32_t)__popcll(bs);
-            if (before < (uint32_t)ke && before + cnt > (uint32_t)kb) {   // wave-uniform
-                const uint32_t pos = before + lanes_below(bs);
-                if (mine && pos >= (uint32_t)kb && pos < (uint32_t)ke) {
-                    const int i = j * kSelThreads + tid;
-                    sh.l_idx[(pos - kb) & (kFusedListCap - 1)] = i;
-                    sh.l_val[(pos - kb) & (kFusedListCap - 1)] = v[j];
-                    if (list_idx) q.idx_out[pos] = i;
-                }
-            }
-            if (scribe && q.mask_out) {
-                const int w0 = j * (kSelThreads / 32) + wave * 2;
-                if (lane == 0 && w0 < nwords) q.mask_out[w0] = (uint32_t)bs;
-                if (lane == 32 && w0 + 1 < nwords) q.mask_out[w0 + 1] = (uint32_t)(bs >> 32);
-            }
-        }
+    // ---- this workgroup's share of the list ---------------------------------------------------
+    // Counts of the keys >= K_lo per (slot, wavefront) tile and their running sums in index
+    // order.  If exactly k keys reach K_lo, no tie is split at the threshold (the usual case):
+    // the selection is key >= K_lo and a selected key's place in the list is the number of such
+    // keys before it.  Only the tiles whose selected keys reach into [kb, ke) are visited: lane j
+    // of a wavefront holds count and running sum of its tile in slot j, and a ballot over "my
+    // tile overlaps the share" is a scalar bit mask that steers the unrolled loop with no vector
+    // work for the tiles that do not.
+    int cnt = 0;
+    TileCount<0, ITEMS>::ge(key, K_lo, cnt);
+    uint32_t n_ge;
+    const uint32_t pre_ge = tile_scan<ITEMS>((uint32_t)cnt, hs, phase, n_ge);
+    const bool fast = n_ge == (uint32_t)p.k;
+    if (fast) {
+        const bool overlap = lane < ITEMS && pre_ge < (uint32_t)ke && pre_ge + (uint32_t)cnt > (uint32_t)kb;
+        const uint64_t active = __ballot(overlap);
+        ListGe<0, ITEMS>::run(key, v, K_lo, (int)pre_ge, active, kb, ke, sh.l_idx, sh.l_val);
     } else {
         uint32_t totals;
         const int pre = (int)tile_prefix_window<ITEMS>(key, K_lo, K_hi, hs, phase, totals);
@@ -222,16 +266,42 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
             const uint64_t bs = __ballot(mine);
             const uint32_t pos = gt_before + min(eq_before, take) + lanes_below(bs);
             if (mine && pos >= (uint32_t)kb && pos < (uint32_t)ke) {
-                const int i = j * kSelThreads + tid;
-                sh.l_idx[(pos - kb) & (kFusedListCap - 1)] = i;
+                sh.l_idx[(pos - kb) & (kFusedListCap - 1)] = j * kSelThreads + tid;
                 sh.l_val[(pos - kb) & (kFusedListCap - 1)] = v[j];
-                if (list_idx) q.idx_out[pos] = i;
             }
-            if (scribe && q.mask_out) {
-                const int w0 = j * (kSelThreads / 32) + wave * 2;
-                if (lane == 0 && w0 < nwords) q.mask_out[w0] = (uint32_t)bs;
-                if (lane == 32 && w0 + 1 < nwords) q.mask_out[w0 + 1] = (uint32_t)(bs >> 32);
+        }
+    }
+
+    // ---- launch-wide outputs of the selection (mask words, index list, scores): off the hot path
+    const bool list_idx = q.idx_out && strip == 0;   // the workgroups of strip 0 cover all of [0, k)
+    if (list_idx) {
+        __syncthreads();
+        for (int t = tid; t < ke - kb; t += kSelThreads) q.idx_out[kb + t] = sh.l_idx[t];
+    }
+    if (scribe && q.mask_out) {
+        uint32_t take = 0u, eq_seen = 0u;
+        if (!fast) {
+            // recount: how many ties are selected, and how many ties precede each tile
+            uint32_t totals;
+            const int pre = (int)tile_prefix_window<ITEMS>(key, K_lo, K_hi, hs, phase, totals);
+            take = (uint32_t)p.k > (totals >> 16) ? (uint32_t)p.k - (totals >> 16) : 0u;
+            eq_seen = (uint32_t)pre;
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            bool mine = key[j] >= K_hi;
+            if (!fast) {
+                const bool tie = key[j] >= K_lo && !mine;
+                const uint64_t be = __ballot(tie);
+                const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)eq_seen, j) & 0xffffu;
+                mine = mine || (tie && eq_before + lanes_below(be) < take);
+            } else {
+                mine = key[j] >= K_lo;
             }
+            const uint64_t bs = __ballot(mine);
+            const int w0 = j * (kSelThreads / 32) + wave * 2;
+            if (lane == 0 && w0 < nwords) q.mask_out[w0] = (uint32_t)bs;
+            if (lane == 32 && w0 + 1 < nwords) q.mask_out[w0 + 1] = (uint32_t)(bs >> 32);
         }
     }
     if (scribe && q.s_out) {

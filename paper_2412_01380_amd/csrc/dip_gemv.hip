@@ -363,8 +363,12 @@ bool fused_shape(int dtype, int n_sel, int n_out, int nseg, int k, GemvShape* sh
     const int epl = elems_per_load(dtype);
     GemvShape best = {0, 16, 0, 4};
     int best_wgs = 0;
-    const int lprs[3] = {32, 64, 16};
-    for (int li = 0; li < 3; ++li) {
+    // Same-box comparisons: 512-byte pieces (32 lanes per row) do as well as 1024-byte ones with
+    // fewer partial sums; 4-bit rows, a quarter of the bytes, do best with the narrowest strip
+    // (longest shares).  The first width that fills 200 of the 256 compute units is taken.
+    const bool q4 = dtype == DIP_INT4_G128;
+    const int lprs[3] = {q4 ? 16 : 32, q4 ? 32 : 64, q4 ? 64 : 16};
+    for (int li = 0; li < 3 && best_wgs < 200; ++li) {
         const int lpr = lprs[li];
         if (g_gemv_override.lpr && g_gemv_override.lpr != lpr) continue;
         if (nseg * lpr * epl > kSelThreads) continue;        // a strip's outputs, one lane each

@@ -373,22 +373,25 @@ __device__ __forceinline__ void finish(const GemvParams& p, float (&acc)[NSEG][E
         }
         __syncthreads();
         if (!s_last) return;
-        // the partial sums of all workgroups, sixteen in flight at a time, added in workgroup order
+        // the partial sums of all workgroups, up to 32 in flight at a time (one round trip to
+        // memory for the usual numbers of workgroups per strip), added in workgroup order
         sum = 0.f;
         if (owner) {
             const float* src0 = p.partial + (size_t)oseg * (size_t)p.n_out + gcol;
             const size_t gstride = (size_t)NSEG * (size_t)p.n_out;
-            for (int g0 = 0; g0 < G; g0 += 16) {
-                float part16[16];
+            constexpr int kInFlight = 32;
+            for (int g0 = 0; g0 < G; g0 += kInFlight) {
+                float part[kInFlight];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int gg = g0 + j < G ? g0 + j : G - 1;
-                    part16[j] = __hip_atomic_load(src0 + (size_t)gg * gstride, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
+                for (int j = 0; j < kInFlight; ++j) {
+                    part[j] = 0.f;
+                    if (g0 + j < G)      // (uniform: G is the same for every lane)
+                        part[j] = __hip_atomic_load(src0 + (size_t)(g0 + j) * gstride, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
                 }
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (g0 + j < G) sum += part16[j];
+                for (int j = 0; j < kInFlight; ++j)
+                    if (g0 + j < G) sum += part[j];
             }
         }
     }

@@ -47,12 +47,16 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SH& sh, int& pha
     phase ^= 1;
     if (lane == 63) tot[wave] = inc;
     __syncthreads();
-    uint32_t base = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t t = tot[w];
-        if (w < wave) base += t;
-    }
+    // Sum of the totals of the wavefronts before this one: lane w < wave takes tot[w], the 16
+    // lanes of row 0 are added with shifts inside the row, and lane 15 holds the sum (a loop
+    // over the 16 totals costs every wavefront four instructions per total).
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    int t = lane < wv ? (int)tot[lane & (kWaves - 1)] : 0;
+    t += __builtin_amdgcn_update_dpp(0, t, 0x111, 0xf, 0xf, false);  // row_shr:1
+    t += __builtin_amdgcn_update_dpp(0, t, 0x112, 0xf, 0xf, false);  // row_shr:2
+    t += __builtin_amdgcn_update_dpp(0, t, 0x114, 0xf, 0xf, false);  // row_shr:4
+    t += __builtin_amdgcn_update_dpp(0, t, 0x118, 0xf, 0xf, false);  // row_shr:8
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readlane(t, 15);
     return base + inc - v;
 }
 

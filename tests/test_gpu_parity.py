@@ -388,6 +388,57 @@ def test_config4_phi3_medium_shape_dip_ca(D, r, frac):
         _stage_replay(D, w, xs[t], k_in, k_mid, TOL["bf16"], (cin, cmid), (ocin, ocmid), cfg.gamma)
 
 
+def test_config4_grid_every_keep_ratio_and_cache_fraction(D):
+    """All 12 cells of the Phi-3-Medium-shaped grid (keep ratio x cache fraction), one layer,
+    two tokens each (the second sees a cache the first has filled); frac 0.25 with r >= 0.25
+    is the regime where the active set exceeds the cache (Sec. 6.4)."""
+    cfg = CONFIGS[4]
+    d, f = cfg.d_model, cfg.d_ff
+    wts = layer_weights(d, f, seed=cfg.seed, layer=2, dtype="bf16")
+    mlp = D.Mlp(make_weight(D, wts["ug"]), make_weight(D, wts["d"]))
+    xs = cfg.tokens(layer=2, n_tokens=2)
+    for r in cfg.keep_ratios:
+        k_in, k_mid = cfg.k_in(r), cfg.k_mid(r)
+        w = {"ug": wts["ug"], "d": wts["d"], "mlp": mlp,
+             "ws": workspace(D.dip_swiglu_mlp_forward_workspace_bytes(mlp, k_in, k_mid)),
+             "dbg": D.Debug(d, f, k_in, k_mid), "y": torch.empty(d, dtype=torch.float32, device="cuda")}
+        for frac in cfg.cache_fracs:
+            C_in, C_mid = int(np.floor(frac * d + 0.5)), int(np.floor(frac * f + 0.5))
+            cin, cmid = D.Cache(d, C_in), D.Cache(f, C_mid)
+            D.dip_cache_init(cin)
+            D.dip_cache_init(cmid)
+            ocin, ocmid = O.CacheState(n=d, capacity=C_in), O.CacheState(n=f, capacity=C_mid)
+            for t in range(2):
+                try:
+                    _stage_replay(D, w, xs[t], k_in, k_mid, TOL["bf16"], (cin, cmid), (ocin, ocmid), cfg.gamma)
+                except AssertionError as e:
+                    raise AssertionError(f"r={r}, cache fraction {frac}, token {t}: {e}") from e
+
+
+def test_config3_long_cache_trace(D):
+    """64 decode tokens of DIP-CA through one Llama-3-8B-shaped layer: every token's masks, sums
+    and both cache states against the oracle (the caches evolve from cold to steady state)."""
+    cfg = CONFIGS[3]
+    d, f = cfg.d_model, cfg.d_ff
+    k_in, k_mid = cfg.k_in(0.3), cfg.k_mid(0.3)
+    w = _setup_layer(D, d, f, "bf16", cfg.seed, 3, k_in, k_mid)
+    cin, cmid = D.Cache(d, d // 2), D.Cache(f, f // 2)
+    D.dip_cache_init(cin)
+    D.dip_cache_init(cmid)
+    ocin, ocmid = O.CacheState(n=d, capacity=d // 2), O.CacheState(n=f, capacity=f // 2)
+    xs = cfg.tokens(layer=3, n_tokens=64)
+    for t in range(64):
+        _stage_replay(D, w, xs[t], k_in, k_mid, TOL["bf16"], (cin, cmid), (ocin, ocmid), cfg.gamma)
+    m_in, m_mid = cin.meta_host(), cmid.meta_host()
+    assert m_in["cum_hits"] == ocin.hits and m_in["cum_lookups"] == ocin.lookups == 64 * k_in
+    assert m_mid["cum_hits"] == ocmid.hits and m_mid["cum_lookups"] == ocmid.lookups == 64 * k_mid
+    # the hit rates the two-tier model reads from the cache states are the oracle's hits / lookups
+    from paper_2412_01380_amd.twotier import hit_rates_from_meta
+    hi, hm = hit_rates_from_meta(m_in, m_mid)
+    assert hi == ocin.hits / ocin.lookups and hm == ocmid.hits / ocmid.lookups
+    assert hi > 0.5 and hm > 0.5          # the AR(1) stream gives the cache something to exploit
+
+
 def test_forward_is_bit_repeatable(D):
     cfg = CONFIGS[2]
     k_in, k_mid = cfg.k_in(0.5), cfg.k_mid(0.5)
