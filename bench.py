@@ -361,6 +361,27 @@ def build_layers(D, cfg, L, workers=6):
     return mlps, host0
 
 
+def timed_repeats(one_block, blocks, repeats, min_repeat_ms):
+    """Time `repeats` repeats of `blocks` blocks each, synchronised on both sides.  A repeat that
+    comes out shorter than the minimum (the pilot block ran slower than the steady state) has its
+    block count raised and the whole set is measured again, so every reported repeat lasts at
+    least `min_repeat_ms`.  Returns (blocks, [seconds per repeat])."""
+    for _ in range(4):
+        times = []
+        for _ in range(max(1, repeats)):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(blocks):
+                one_block()
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        short = min(times) * 1e3
+        if short >= min_repeat_ms:
+            break
+        blocks = int(np.ceil(blocks * 1.15 * min_repeat_ms / max(short, 1e-3)))
+    return blocks, times
+
+
 def hit_rates(D, cins, cmids, before=None):
     """Hit rates from the cache states' own counters (dip_cache.meta) through the two-tier
     model's reader; `before` = an earlier reading to take the difference with."""
@@ -498,16 +519,23 @@ def main():
     run.run(K)
     torch.cuda.synchronize()
     pilot = time.perf_counter() - t0
-    blocks = max(1, int(np.ceil(a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
+    blocks = max(1, int(np.ceil(1.25 * a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
     hr_before = hit_rates(D, cins, cmids)[0] if use_cache else None
-    times = []
-    for _ in range(max(1, a.repeats)):
+    one_block = lambda: run.run(K)            # exactly K layer-steps
+    launch_mode = "launches issued from the host through dip_swiglu_mlp_forward_stack"
+    if a.graph:
+        # The launches of one block are captured once into a HIP graph (the library only
+        # launches kernels on the given stream: no allocation, no memset, no host
+        # synchronisation) and the block is replayed: same kernels, same arguments, same
+        # tokens.  Cache state lives in device memory and keeps evolving from replay to replay.
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run.run(K)
+        graph.replay()                        # one untimed replay
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(blocks):
-            run.run(K)            # exactly K layer-steps
-        torch.cuda.synchronize()
-        times.append(time.perf_counter() - t0)
+        one_block = graph.replay
+        launch_mode = f"HIP graph of one block of {K} steps, replayed"
+    blocks, times = timed_repeats(one_block, blocks, a.repeats, a.min_repeat_ms)
     wall = statistics.median(times)
     ms_per_step = wall / (blocks * K) * 1e3
     steps_per_s = 1e3 / ms_per_step
@@ -540,7 +568,7 @@ def main():
             "step": f"one token through one MLP layer ({launches} kernel launches"
                     + (", cache updates of a token's layers batched into one more" if use_cache else "") + ")",
             "batch": 1,
-            "launch": "launches issued from the host through dip_swiglu_mlp_forward_stack",
+            "launch": launch_mode,
         },
         "timing": {"repeats": len(times), "blocks_per_repeat": blocks, "steps_per_block": K,
                    "repeat_ms": [t * 1e3 for t in times], "statistic": "median of repeats",
@@ -672,6 +700,7 @@ def main():
 def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gamma, k_in, k_mid, t_setup):
     """Config 5 at batch B > 1: B rows per step through one layer, columns read once per step
     if any row selected them.  Bytes are the MEASURED union sizes times the column sizes."""
+    import ctypes as C
     import numpy as np
     import statistics
     import torch
@@ -682,20 +711,41 @@ def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gam
     # row b of layer l at step t is its own stream: shifted copies of the layer's stream
     Xb = torch.stack([Xd[(torch.arange(n_tok) + 37 * b) % n_tok] for b in range(B)], dim=2).contiguous()
     Yb = torch.empty(L, B, d, dtype=torch.float32, device="cuda")
-    ws = torch.empty(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[0], B, k_in, k_mid),
-                     dtype=torch.uint8, device="cuda")
+    ws1 = torch.empty(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[0], B, k_in, k_mid),
+                      dtype=torch.uint8, device="cuda")
     wd, wf = (d + 31) // 32, (f + 31) // 32
     m_in = torch.zeros(B, wd, dtype=torch.int32, device="cuda")
     m_mid = torch.zeros(B, wf, dtype=torch.int32, device="cuda")
     pos = [0]
+    ranges = {}
+    full = D.MlpStack(mlps, cins, cmids)
+    ws = torch.empty(D.dip_swiglu_mlp_forward_batched_stack_workspace_bytes(full, B, k_in, k_mid),
+                     dtype=torch.uint8, device="cuda")
+
+    def stack(l0, l1):
+        if (l0, l1) not in ranges:
+            m = l1 - l0
+            ranges[(l0, l1)] = (D.MlpStack(mlps[l0:l1], cins[l0:l1] if use_cache else None,
+                                           cmids[l0:l1] if use_cache else None),
+                                (C.c_int32 * m)(*([k_in] * m)), (C.c_int32 * m)(*([k_mid] * m)))
+        return ranges[(l0, l1)]
 
     def run(n, masks=False):
-        for _ in range(n):
+        """n layer-steps, token-major; each range of layers of one token is one call of the batched
+        stack entry point (with `masks`: one layer per call, so that its row masks can be read)."""
+        while n > 0:
             t, l = divmod(pos[0], L)
-            D.dip_swiglu_mlp_forward_batched(mlps[l], Xb[t % n_tok, l], B, k_in, k_mid,
-                                             cins[l] if use_cache else None, cmids[l] if use_cache else None,
-                                             gamma, Yb[l], m_in if masks else None, None, m_mid if masks else None, ws)
-            pos[0] += 1
+            if masks:
+                D.dip_swiglu_mlp_forward_batched(mlps[l], Xb[t % n_tok, l], B, k_in, k_mid,
+                                                 cins[l] if use_cache else None, cmids[l] if use_cache else None,
+                                                 gamma, Yb[l], m_in, None, m_mid, ws1)
+                m = 1
+            else:
+                m = min(n, L - l)
+                st, ki, km = stack(l, l + m)
+                D.dip_swiglu_mlp_forward_batched_stack(st, Xb[t % n_tok, l:], B * d, B, ki, km, gamma, Yb[l:], B * d, ws)
+            pos[0] += m
+            n -= m
 
     K, W = max(1, a.steps), max(0, a.warmup)
     run(W)
@@ -705,15 +755,8 @@ def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gam
     run(K)
     torch.cuda.synchronize()
     pilot = time.perf_counter() - t0
-    blocks = max(1, int(np.ceil(a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
-    times = []
-    for _ in range(max(1, a.repeats)):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(blocks):
-            run(K)
-        torch.cuda.synchronize()
-        times.append(time.perf_counter() - t0)
+    blocks = max(1, int(np.ceil(1.25 * a.min_repeat_ms * 1e-3 / max(pilot, 1e-6))))
+    blocks, times = timed_repeats(lambda: run(K), blocks, a.repeats, a.min_repeat_ms)
     wall = statistics.median(times)
     ms_per_step = wall / (blocks * K) * 1e3
 
@@ -758,7 +801,7 @@ def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gam
             "inputs": cfg.inputs, "weights_dtype": cfg.dtype, "batch": B,
             "measured_union_columns": {"in": u_in, "mid": u_mid, "of": [d, f], "sample_steps": ns},
             "gathered_bytes_per_step": gathered,
-            "step": f"{B} rows through one MLP layer (dip_swiglu_mlp_forward_batched)",
+            "step": f"{B} rows through one MLP layer (dip_swiglu_mlp_forward_batched_stack over the layers of a token)",
         },
         "timing": {"repeats": len(times), "blocks_per_repeat": blocks, "steps_per_block": K,
                    "repeat_ms": [t * 1e3 for t in times], "statistic": "median of repeats"},

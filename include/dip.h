@@ -337,6 +337,22 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
                                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The batched forward for n_layers independent layers in one call: layer l reads its `batch`
+ * rows at X + l * x_stride ([batch][d_model], contiguous) and writes Y + l * y_stride (strides
+ * in floats), with k_in[l] / k_mid[l] kept per row (host arrays).  Cache rules as in
+ * dip_swiglu_mlp_forward_stack: one dip_cache per layer and point, all updated -- once each,
+ * with the union of the layer's row masks -- in one launch at the end of the call.
+ */
+size_t dip_swiglu_mlp_forward_batched_stack_workspace_bytes(const dip_mlp* mlps, int32_t n_layers, int32_t batch,
+                                                            const int32_t* k_in /* host */,
+                                                            const int32_t* k_mid /* host */);
+int32_t dip_swiglu_mlp_forward_batched_stack(const dip_mlp* mlps, int32_t n_layers, const float* X,
+                                             int64_t x_stride, int32_t batch, const int32_t* k_in /* host */,
+                                             const int32_t* k_mid /* host */, const dip_cache* caches_in,
+                                             const dip_cache* caches_mid, float gamma, float* Y,
+                                             int64_t y_stride, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * GLU pruning, Sec. 3.2: W^u x and W^g x are dense, m = topK(|GLU(x)|, k) removes columns
  * of W^d:  y = sum_{i in m} W^d[:, i] GLU(x)_i.  Same matrices, layout and workspace rules
  * as dip_swiglu_mlp_forward; x must be 16-byte aligned; the point-1 members of dbg must be NULL.

@@ -20,5 +20,6 @@ from .libdip import (  # noqa: F401
     DIP_GATE_PRUNING, DIP_UP_PRUNING, MlpSplit, PartialDebug, glu_debug, dip_glu_pruning_forward,
     dip_glu_pruning_forward_workspace_bytes, dip_gathered_rowdot, dip_partial_pruning_forward,
     dip_partial_pruning_forward_workspace_bytes,
-    dip_swiglu_mlp_forward_batched, dip_swiglu_mlp_forward_batched_workspace_bytes, dip_profile_read, dip_profile_disable,
+    dip_swiglu_mlp_forward_batched, dip_swiglu_mlp_forward_batched_workspace_bytes,
+    dip_swiglu_mlp_forward_batched_stack, dip_swiglu_mlp_forward_batched_stack_workspace_bytes, dip_profile_read, dip_profile_disable,
 )

@@ -566,7 +566,7 @@ namespace {
 struct BatchedPlan {
     int d, f, wd, wf, k1max, k2max, g1, g2;
     bool mc1, mc2;             // product on the matrix cores
-    size_t off_rmax, off_m1, off_u1, off_idx1, off_val1, off_m2, off_u2, off_idx2, off_val2, off_cnt, off_h,
+    size_t off_rmax, off_m1, off_idx1, off_val1, off_m2, off_idx2, off_val2, off_cnt, off_h,
         off_part;
     size_t total;
 };
@@ -584,12 +584,10 @@ BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     pl.off_rmax = take(sizeof(uint32_t) * 16);     // per point: 8 row maxima
     pl.off_m1 = take(sizeof(uint32_t) * B * pl.wd);
-    pl.off_u1 = take(sizeof(uint32_t) * pl.wd);
     // index and multiplier lists carry 16 spare entries: the product reads whole vectors
     pl.off_idx1 = take(sizeof(int32_t) * (pl.k1max + 16));
     pl.off_val1 = take(sizeof(float) * (size_t)(pl.k1max + 16) * B);
     pl.off_m2 = take(sizeof(uint32_t) * B * pl.wf);
-    pl.off_u2 = take(sizeof(uint32_t) * pl.wf);
     pl.off_idx2 = take(sizeof(int32_t) * (pl.k2max + 16));
     pl.off_val2 = take(sizeof(float) * (size_t)(pl.k2max + 16) * B);
     pl.off_cnt = take(sizeof(uint32_t) * 2);
@@ -602,31 +600,33 @@ BatchedPlan plan_batched(const dip_mlp* mlp, int B, int k_in, int k_mid) {
 }
 }  // namespace
 
+// Workspace of the batched calls: [ union mask words of every layer: point 1, point 2 ] kept
+// until the cache updates at the end of the call, then the scratch of one layer.
 size_t dip_swiglu_mlp_forward_batched_workspace_bytes(const dip_mlp* mlp, int32_t batch,
                                                       int32_t k_in, int32_t k_mid) {
     if (batch < 1 || batch > 8 || validate_mlp(mlp, k_in, k_mid)) return 0;
-    return plan_batched(mlp, batch, k_in, k_mid).total;
+    return 2 * kMaskBytes + plan_batched(mlp, batch, k_in, k_mid).total;
 }
 
-int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32_t batch,
-                                       int32_t k_in, int32_t k_mid, const dip_cache* cache_in,
-                                       const dip_cache* cache_mid, float gamma, float* Y,
-                                       uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out,
-                                       void* ws, size_t ws_bytes, void* stream) {
-    if (batch < 1 || batch > 8) return fail(DIP_ERR_INVALID_ARG, "forward_batched: batch must be in [1, 8]");
-    int32_t st = validate_mlp(mlp, k_in, k_mid);
-    if (st) return st;
-    if (!X || !Y) return fail(DIP_ERR_INVALID_ARG, "forward_batched: null X or Y");
-    if (cache_in || cache_mid) {
-        if ((st = validate_gamma(gamma))) return st;
+size_t dip_swiglu_mlp_forward_batched_stack_workspace_bytes(const dip_mlp* mlps, int32_t n_layers, int32_t batch,
+                                                            const int32_t* k_in, const int32_t* k_mid) {
+    if (!mlps || !k_in || !k_mid || n_layers < 1 || batch < 1 || batch > 8) return 0;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (validate_mlp(&mlps[l], k_in[l], k_mid[l])) return 0;
+        need = std::max(need, plan_batched(&mlps[l], batch, k_in[l], k_mid[l]).total);
     }
-    if (cache_in && (st = validate_cache(cache_in, mlp->w_ug.n_in, "cache_in"))) return st;
-    if (cache_mid && (st = validate_cache(cache_mid, mlp->w_d.n_in, "cache_mid"))) return st;
-    const BatchedPlan pl = plan_batched(mlp, batch, k_in, k_mid);
-    if (!ws || ws_bytes < pl.total || !aligned(ws, 256))
-        return fail(DIP_ERR_WORKSPACE, "forward_batched: workspace must be 256-aligned and >= %zu bytes", pl.total);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    char* base = static_cast<char*>(ws);
+    return (size_t)n_layers * 2 * kMaskBytes + need;
+}
+
+namespace {
+// `batch` rows through one layer; the union masks go to uw1 / uw2 and the cache updates with
+// them are left to the caller (one launch at the end of the call).
+int32_t batched_one(const dip_mlp* mlp, const BatchedPlan& pl, const float* X, int batch, int k_in, int k_mid,
+                    const dip_cache* cache_in, const dip_cache* cache_mid, float gamma, float* Y,
+                    uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out, char* base, uint32_t* uw1,
+                    uint32_t* uw2, hipStream_t hs, std::vector<UpdatePiece>& updates) {
+    int32_t st = DIP_OK;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(base + pl.off_cnt);
     float* H = h_out ? h_out : reinterpret_cast<float*>(base + pl.off_h);
     float* part = reinterpret_cast<float*>(base + pl.off_part);
@@ -637,17 +637,13 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
     };
     const Point pts[2] = {
         {X, pl.d, k_in, pl.k1max, pl.wd, cache_in,
-         mask_in_out ? mask_in_out : reinterpret_cast<uint32_t*>(base + pl.off_m1),
-         reinterpret_cast<uint32_t*>(base + pl.off_u1), reinterpret_cast<int32_t*>(base + pl.off_idx1),
-         reinterpret_cast<float*>(base + pl.off_val1), cnt, DIP_KERNEL_SELECT_IN},
+         mask_in_out ? mask_in_out : reinterpret_cast<uint32_t*>(base + pl.off_m1), uw1,
+         reinterpret_cast<int32_t*>(base + pl.off_idx1), reinterpret_cast<float*>(base + pl.off_val1), cnt,
+         DIP_KERNEL_SELECT_IN},
         {H, pl.f, k_mid, pl.k2max, pl.wf, cache_mid,
-         mask_mid_out ? mask_mid_out : reinterpret_cast<uint32_t*>(base + pl.off_m2),
-         reinterpret_cast<uint32_t*>(base + pl.off_u2), reinterpret_cast<int32_t*>(base + pl.off_idx2),
-         reinterpret_cast<float*>(base + pl.off_val2), cnt + 1, DIP_KERNEL_SELECT_MID}};
-    // The cache update of a point is not needed by anything in this step: the one of point 1
-    // rides along the row selection of point 2, the one of point 2 is launched at the end.
-    SelectParams deferred;
-    bool have_deferred = false;
+         mask_mid_out ? mask_mid_out : reinterpret_cast<uint32_t*>(base + pl.off_m2), uw2,
+         reinterpret_cast<int32_t*>(base + pl.off_idx2), reinterpret_cast<float*>(base + pl.off_val2), cnt + 1,
+         DIP_KERNEL_SELECT_MID}};
     for (int pt = 0; pt < 2; ++pt) {
         const Point& q = pts[pt];
         // per-row scores and masks (state of the cache from before the step)
@@ -656,27 +652,22 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         sp.v = q.v; sp.n = q.n; sp.k = q.k; sp.gamma = gamma;
         sp.score_bits = q.cache ? q.cache->bits : nullptr;
         sp.mask_out = q.masks; sp.rows = batch; sp.v_row_stride = q.n; sp.words_row_stride = q.words;
+        const bool mc = pt == 0 ? pl.mc1 : pl.mc2;
         uint32_t* rowmax = reinterpret_cast<uint32_t*>(base + pl.off_rmax) + 8 * pt;
-        sp.zero_ptr = rowmax; sp.zero_n = 8;       // the union kernel below takes maxima into it
-        if ((st = check_hip(launch_select(sp, hs, q.kind, have_deferred ? &deferred : nullptr),
-                            "forward_batched: select")))
-            return st;
-        have_deferred = false;
+        sp.rowmax_out = mc ? rowmax : nullptr;     // max |x| per row, for the matrix-core product's scaling
+        if ((st = check_hip(launch_select(sp, hs, q.kind), "forward_batched: select"))) return st;
         // union of the row masks, its index list and the row multipliers
         UnionParams up;
         std::memset(&up, 0, sizeof(up));
         up.masks = q.masks; up.words_stride = q.words; up.x = q.v; up.x_stride = q.n; up.n = q.n;
         up.batch = batch; up.union_words = q.uwords; up.uidx = q.uidx; up.uval = q.uval; up.count_out = q.count;
-        const bool mc = pt == 0 ? pl.mc1 : pl.mc2;
-        up.rowmax = mc ? rowmax : nullptr;
         if ((st = check_hip(launch_union(up, hs), "forward_batched: union"))) return st;
-        // one cache update with the union mask
+        // one cache update with the union mask (Alg. 1 step 3), run by the caller
         if (q.cache) {
-            std::memset(&deferred, 0, sizeof(deferred));
-            deferred.n = q.n; deferred.k = 1; deferred.mask_in = q.uwords;
-            deferred.c_bits = q.cache->bits; deferred.c_stamp = q.cache->stamp; deferred.c_meta = q.cache->meta;
-            deferred.capacity = q.cache->capacity; deferred.policy = q.cache->policy;
-            have_deferred = true;
+            UpdatePiece u;
+            u.mask = q.uwords; u.bits = q.cache->bits; u.stamp = q.cache->stamp; u.meta = q.cache->meta;
+            u.n = q.n; u.capacity = q.cache->capacity; u.policy = q.cache->policy; u.pad = 0;
+            updates.push_back(u);
         }
         // gathered product for all rows, then the reduction with its epilogue
         const dip_weight& w = pt == 0 ? mlp->w_ug : mlp->w_d;
@@ -697,9 +688,79 @@ int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32
         rp.out = pt == 0 ? H : Y; rp.out_stride = pt == 0 ? pl.f : pl.d;
         if ((st = check_hip(launch_batched_reduce(rp, hs), "forward_batched: reduction"))) return st;
     }
-    if (have_deferred)
-        return check_hip(launch_select(deferred, hs, DIP_KERNEL_CACHE_UPDATE), "forward_batched: cache update");
     return DIP_OK;
+}
+
+int32_t batched_checked(const dip_mlp* mlps, int n_layers, const float* X, int64_t x_stride, int batch,
+                        const int32_t* k_in, const int32_t* k_mid, int k_stride, const dip_cache* caches_in,
+                        const dip_cache* caches_mid, float gamma, float* Y, int64_t y_stride,
+                        uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out, void* ws, size_t ws_bytes,
+                        void* stream) {
+    if (batch < 1 || batch > 8) return fail(DIP_ERR_INVALID_ARG, "forward_batched: batch must be in [1, 8]");
+    if (!mlps) return fail(DIP_ERR_INVALID_ARG, "forward_batched: null mlp descriptor");
+    if (n_layers < 1) return fail(DIP_ERR_INVALID_ARG, "forward_batched: n_layers must be >= 1");
+    if (!X || !Y) return fail(DIP_ERR_INVALID_ARG, "forward_batched: null X or Y");
+    if (!k_in || !k_mid) return fail(DIP_ERR_INVALID_ARG, "forward_batched: null k_in or k_mid");
+    int32_t st = DIP_OK;
+    if (caches_in || caches_mid) {
+        if ((st = validate_gamma(gamma))) return st;
+    }
+    size_t need = 0;
+    std::vector<const uint32_t*> seen;
+    for (int l = 0; l < n_layers; ++l) {
+        if ((st = validate_mlp(&mlps[l], k_in[l * k_stride], k_mid[l * k_stride]))) return st;
+        if (caches_in && (st = validate_cache(&caches_in[l], mlps[l].w_ug.n_in, "cache_in"))) return st;
+        if (caches_mid && (st = validate_cache(&caches_mid[l], mlps[l].w_d.n_in, "cache_mid"))) return st;
+        if (caches_in) seen.push_back(caches_in[l].bits);
+        if (caches_mid) seen.push_back(caches_mid[l].bits);
+        need = std::max(need, plan_batched(&mlps[l], batch, k_in[l * k_stride], k_mid[l * k_stride]).total);
+    }
+    std::sort(seen.begin(), seen.end());
+    if (std::adjacent_find(seen.begin(), seen.end()) != seen.end())
+        return fail(DIP_ERR_INVALID_ARG, "forward_batched: two pruning points share one cache state (every layer "
+                                         "and point needs a dip_cache of its own)");
+    const size_t mask_bytes = (size_t)n_layers * 2 * kMaskBytes;
+    need += mask_bytes;
+    if (!ws || ws_bytes < need || !aligned(ws, 256))
+        return fail(DIP_ERR_WORKSPACE, "forward_batched: workspace must be 256-aligned and >= %zu bytes", need);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    std::vector<UpdatePiece> updates;
+    updates.reserve(2 * (size_t)n_layers);
+    for (int l = 0; l < n_layers && !st; ++l) {
+        const int ki = k_in[l * k_stride], km = k_mid[l * k_stride];
+        const BatchedPlan pl = plan_batched(&mlps[l], batch, ki, km);
+        st = batched_one(&mlps[l], pl, X + (int64_t)l * x_stride, batch, ki, km,
+                         caches_in ? &caches_in[l] : nullptr, caches_mid ? &caches_mid[l] : nullptr, gamma,
+                         Y + (int64_t)l * y_stride, mask_in_out, h_out, mask_mid_out, base + mask_bytes,
+                         reinterpret_cast<uint32_t*>(base + (size_t)(2 * l) * kMaskBytes),
+                         reinterpret_cast<uint32_t*>(base + (size_t)(2 * l + 1) * kMaskBytes), hs, updates);
+    }
+    if (!updates.empty()) {
+        const int32_t st2 = check_hip(launch_update_batch(updates.data(), (int)updates.size(), hs, DIP_KERNEL_CACHE_UPDATE),
+                                      "forward_batched: cache updates");
+        if (!st) st = st2;
+    }
+    return st;
+}
+}  // namespace
+
+int32_t dip_swiglu_mlp_forward_batched(const dip_mlp* mlp, const float* X, int32_t batch,
+                                       int32_t k_in, int32_t k_mid, const dip_cache* cache_in,
+                                       const dip_cache* cache_mid, float gamma, float* Y,
+                                       uint32_t* mask_in_out, float* h_out, uint32_t* mask_mid_out,
+                                       void* ws, size_t ws_bytes, void* stream) {
+    return batched_checked(mlp, 1, X, 0, batch, &k_in, &k_mid, 0, cache_in, cache_mid, gamma, Y, 0, mask_in_out,
+                           h_out, mask_mid_out, ws, ws_bytes, stream);
+}
+
+int32_t dip_swiglu_mlp_forward_batched_stack(const dip_mlp* mlps, int32_t n_layers, const float* X,
+                                             int64_t x_stride, int32_t batch, const int32_t* k_in,
+                                             const int32_t* k_mid, const dip_cache* caches_in,
+                                             const dip_cache* caches_mid, float gamma, float* Y,
+                                             int64_t y_stride, void* ws, size_t ws_bytes, void* stream) {
+    return batched_checked(mlps, n_layers, X, x_stride, batch, k_in, k_mid, 1, caches_in, caches_mid, gamma, Y,
+                           y_stride, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int32_t dip_tune_gemv(int32_t lanes_per_row, int32_t waves, int32_t ksplit, int32_t unroll) {

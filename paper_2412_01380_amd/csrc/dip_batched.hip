@@ -71,32 +71,19 @@ __global__ __launch_bounds__(kUnionThreads) void union_kernel(UnionParams p) {
     __syncthreads();
 
     const int w = blockIdx.x * kUnionWordsPerWg + (tid >> 5), bit = tid & 31;
+    if (w >= nwords) return;
     uint32_t rows = 0, uw = 0;    // bit b of rows: row b selected this feature
-    for (int b = 0; b < p.batch && w < nwords; ++b) {
+    for (int b = 0; b < p.batch; ++b) {
         const uint32_t m = p.masks[(size_t)b * p.words_stride + w];
         uw |= m;
         rows |= ((m >> bit) & 1u) << b;
     }
-    if (rows) {
-        const uint32_t pos = s_base[w] + (uint32_t)__popc(uw & ((1u << bit) - 1u));
-        const int i = w * 32 + bit;
-        p.uidx[pos] = i;
-        for (int b = 0; b < p.batch; ++b) {
-            const float xv = ((rows >> b) & 1u) ? p.x[(size_t)b * p.x_stride + i] : 0.f;
-            p.uval[(size_t)pos * p.batch + b] = xv;
-        }
-    }
-    // largest |multiplier| of every row (bit patterns of non-negative floats order like
-    // integers): one integer atomic per wavefront and row, zero on entry
-    if (p.rowmax) {
-        for (int b = 0; b < p.batch; ++b) {
-            uint32_t a = 0u;
-            if ((rows >> b) & 1u) a = __float_as_uint(fabsf(p.x[(size_t)b * p.x_stride + w * 32 + bit]));
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) a = max(a, (uint32_t)__shfl_xor((int)a, off));
-            if (lane == 0 && a) atomicMax(&p.rowmax[b], a);
-        }
-    }
+    if (!rows) return;
+    const uint32_t pos = s_base[w] + (uint32_t)__popc(uw & ((1u << bit) - 1u));
+    const int i = w * 32 + bit;
+    p.uidx[pos] = i;
+    for (int b = 0; b < p.batch; ++b)
+        p.uval[(size_t)pos * p.batch + b] = ((rows >> b) & 1u) ? p.x[(size_t)b * p.x_stride + i] : 0.f;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -334,7 +321,7 @@ __global__ __launch_bounds__(kBWaves * 64) void bgemv_kernel(BatchedGemvParams p
 // sum of two fp16 numbers (its rounded value and the rounded rest; each tile is multiplied
 // twice).  fp16 has a fixed range, and the re-weighting of Sec. 5.2 normalises by ||x||_inf
 // precisely so that the dynamic range of the activations does not matter: every batch row is
-// therefore multiplied by the power of two that brings its largest |multiplier| into [8, 16)
+// therefore multiplied by the power of two that brings its largest |activation| into [8, 16)
 // before the split -- exact in fp32 -- and the partial sums are multiplied by the inverse
 // power when they are stored, also exact.  The product then depends on the weights only:
 // with |m| < 16 it stays inside the fp16 range for group scales up to 4094, and the second
@@ -367,7 +354,7 @@ __device__ __forceinline__ h4_t pack_h4(float a, float b, float c, float d) {
     return __builtin_bit_cast(h4_t, v);
 }
 
-// The power of two that brings a row's largest |multiplier| (given as its bit pattern) into
+// The power of two that brings a row's largest |activation| (given as its bit pattern) into
 // [8, 16); 1 for an all-zero row.  Denormal and near-overflow maxima are clamped to factors
 // fp32 can hold; such rows only lose the part of the range fp16 could not carry anyway.
 __device__ __forceinline__ float row_scale_up(uint32_t max_bits) {

@@ -61,15 +61,15 @@ struct SelectParams {
     uint32_t* evicted_out;
     uint32_t* inserted_out;
     // rows > 1: one workgroup per row; row b reads v + b*v_row_stride and writes its mask at
-    // mask_out + b*words_row_stride (every other output and the cache update must be off)
+    // mask_out + b*words_row_stride (the other outputs and the cache update must be off)
     int rows;
     int64_t v_row_stride;
     int64_t words_row_stride;
+    // nullable: row b (one workgroup per row; row 0 otherwise) writes the bit pattern of max |v| here
+    uint32_t* rowmax_out;
 };
 
-// `second`, `third`: independent single-row work for further workgroups of the same launch
-hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind,
-                         const SelectParams* second = nullptr, const SelectParams* third = nullptr);
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind);
 
 // Cache updates of several caches in one launch, one workgroup each (nothing in the token
 // that produced the masks waits for them).
@@ -195,7 +195,6 @@ struct UnionParams {
     int32_t* uidx;             // ascending indices of the union, up to min(n, batch*k)
     float* uval;               // [listed][batch]: x[b][i] if row b selected i, else 0
     uint32_t* count_out;       // number of listed indices
-    uint32_t* rowmax;          // [batch], zero on entry: bit pattern of the largest |x[b][i]| listed for row b; nullable
 };
 struct BatchedGemvParams {
     const void* w;
@@ -211,7 +210,7 @@ struct BatchedGemvParams {
     int k_max;                 // capacity of the lists
     int batch;
     float* partial;            // [shares][batch][n_out]
-    const uint32_t* rowmax;    // [batch] from the union kernel (matrix-core product only)
+    const uint32_t* rowmax;    // [batch] bit patterns of max |x[b]| from the row selection (matrix-core product only)
 };
 struct BatchedReduceParams {
     const float* partial;

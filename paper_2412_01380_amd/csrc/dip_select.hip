@@ -16,12 +16,16 @@
 // (stamp, index) first) are the largest ages (current step - stamp) among the evictable
 // columns, found by the same radix select.
 //
-// The kernel is bound by instruction issue on its one compute unit (16 wavefronts share 4
-// SIMDs: every instruction executed per key costs 16 cycles of the workgroup), not by LDS
-// atomics or memory, so each stage is written for the fewest instructions per key: plain
-// histogram adds with the tie-storm handling hoisted out of the per-key path, branch-free
-// clamped loads, one compare per key on the usual path where no tie is split at the
-// threshold.
+// The kernel runs on one compute unit and is bound by what that unit does in sequence: the
+// instructions per key (16 wavefronts share 4 SIMDs: every instruction executed per key costs
+// 16 cycles of the workgroup), the LDS adds of the first radix digit (the keys of an
+// activation vector crowd into a few dozen bins) and a dozen barrier-separated LDS round
+// trips.  Each stage is therefore written for the fewest instructions per key: plain histogram
+// adds with the tie-storm handling hoisted out of the per-key path, branch-free clamped
+// loads, one compare per key on the usual path where no tie is split at the threshold.
+// The forward calls run the same selection at the head of the gathered products instead
+// (dip_fused.hip); this kernel serves the stand-alone entry points, the batched rows, the
+// two-tier path and, through update_batch_kernel, every cache update.
 #include "dip_select_device.h"
 
 namespace dip {
@@ -74,13 +78,6 @@ struct SelectGe {
         write_lane<(2 * J + 1) & 63>(my_word, (uint32_t)(bs >> 32));
         if constexpr (J + 1 < ITEMS) SelectGe<J + 1, ITEMS, EMIT>::run(key, v, T, pre, idx_out, val_out, k, sel, my_word);
     }
-};
-
-// A launch may carry independent pieces of work for further workgroups (blockIdx.y = 1, 2):
-// cache updates of earlier pruning points, which nothing in this token waits for, next to
-// this point's scores and top-K.
-struct SelectWork {
-    SelectParams piece[3];
 };
 
 template <int ITEMS>
@@ -139,7 +136,8 @@ __device__ __forceinline__ void select_body(SelectParams& p, SelShared& sh) {
 
     if (!p.mask_in) {
         // ---- Alg. 1 step 1: scores --------------------------------------------------
-        if (p.score_bits) {
+        float M = 0.f;
+        if (p.score_bits || p.rowmax_out) {
             float m = 0.f;
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) m = fmaxf(m, fabsf(v[j]));
@@ -147,9 +145,11 @@ __device__ __forceinline__ void select_body(SelectParams& p, SelShared& sh) {
             for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
             if (lane == 0) sh.wave_max[wave] = m;
             __syncthreads();
-            float M = 0.f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sh.wave_max[w]);
+            if (p.rowmax_out && tid == 0) p.rowmax_out[0] = __float_as_uint(M);
+        }
+        if (p.score_bits) {
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) {
                 const float a = fabsf(v[j]);
@@ -396,14 +396,12 @@ __device__ __forceinline__ void select_body(SelectParams& p, SelShared& sh) {
 }
 
 template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectWork work) {
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     __shared__ SelShared sh;
-    // (indexed in the kernel argument segment: only this workgroup's piece is loaded)
-    SelectParams p = work.piece[blockIdx.y];
-    if (blockIdx.y > 0 && blockIdx.x > 0) return;   // the extra work is never a batch of rows
     // one workgroup per row of a small batch (row 0 when there is no batch)
     if (p.v) p.v += (size_t)blockIdx.x * p.v_row_stride;
     if (p.mask_out) p.mask_out += (size_t)blockIdx.x * p.words_row_stride;
+    if (p.rowmax_out) p.rowmax_out += blockIdx.x;
     select_body<ITEMS>(p, sh);
 }
 
@@ -422,7 +420,7 @@ __global__ __launch_bounds__(kSelThreads) void update_batch_kernel(UpdateWork wo
     p.idx_out = nullptr; p.val_out = nullptr;
     p.c_bits = u.bits; p.c_stamp = u.stamp; p.c_meta = u.meta; p.capacity = u.capacity; p.policy = u.policy;
     p.zero_ptr = nullptr; p.zero_n = 0; p.evicted_out = nullptr; p.inserted_out = nullptr;
-    p.rows = 1; p.v_row_stride = 0; p.words_row_stride = 0;
+    p.rows = 1; p.v_row_stride = 0; p.words_row_stride = 0; p.rowmax_out = nullptr;
     select_body<ITEMS>(p, sh);
 }
 
@@ -457,20 +455,8 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 }
 
 template <int ITEMS>
-hipError_t launch_items(const SelectParams& p, const SelectParams* second, const SelectParams* third,
-                        hipStream_t stream, int prof_kind) {
-    const dim3 grid(p.rows > 1 ? p.rows : 1, third ? 3 : (second ? 2 : 1));
-    SelectWork work;
-    work.piece[0] = p;
-    work.piece[1] = second ? *second : p;
-    work.piece[2] = third ? *third : p;
-    hipEvent_t e0, e1;
-    if (prof_kind >= 0 && prof_next(prof_kind, &e0, &e1)) {
-        hipExtLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, e0, e1, 0, work);
-    } else {
-        hipLaunchKernelGGL(select_kernel<ITEMS>, grid, dim3(kSelThreads), 0, stream, work);
-    }
-    return hipGetLastError();
+hipError_t launch_items(const SelectParams& p, hipStream_t stream, int prof_kind) {
+    return launch_timed(select_kernel<ITEMS>, dim3(p.rows > 1 ? p.rows : 1), dim3(kSelThreads), stream, prof_kind, p);
 }
 
 template <int ITEMS>
@@ -503,32 +489,25 @@ hipError_t launch_update_batch(const UpdatePiece* pieces, int count, hipStream_t
     return hipSuccess;
 }
 
-hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind, const SelectParams* second,
-                         const SelectParams* third) {
-    // all pieces of work run the same instantiation: the one that fits the longest vector
-    if (third && !second) return hipErrorInvalidValue;
-    if ((second && second->rows > 1) || (third && third->rows > 1)) return hipErrorInvalidValue;
-    int n = p.n;
-    if (second && second->n > n) n = second->n;
-    if (third && third->n > n) n = third->n;
-    const int items = (n + kSelThreads - 1) / kSelThreads;
+hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind) {
+    const int items = (p.n + kSelThreads - 1) / kSelThreads;
     switch (items) {
-        case 1: return launch_items<1>(p, second, third, stream, prof_kind);
-        case 2: return launch_items<2>(p, second, third, stream, prof_kind);
-        case 3: return launch_items<3>(p, second, third, stream, prof_kind);
-        case 4: return launch_items<4>(p, second, third, stream, prof_kind);
-        case 5: return launch_items<5>(p, second, third, stream, prof_kind);
-        case 6: return launch_items<6>(p, second, third, stream, prof_kind);
-        case 7: case 8: return launch_items<8>(p, second, third, stream, prof_kind);
-        case 9: case 10: return launch_items<10>(p, second, third, stream, prof_kind);
-        case 11: case 12: return launch_items<12>(p, second, third, stream, prof_kind);
-        case 13: case 14: return launch_items<14>(p, second, third, stream, prof_kind);
-        case 15: case 16: return launch_items<16>(p, second, third, stream, prof_kind);
-        case 17: case 18: return launch_items<18>(p, second, third, stream, prof_kind);
-        case 19: case 20: return launch_items<20>(p, second, third, stream, prof_kind);
-        case 21: case 22: case 23: case 24: return launch_items<24>(p, second, third, stream, prof_kind);
-        case 25: case 26: case 27: case 28: return launch_items<28>(p, second, third, stream, prof_kind);
-        default: return launch_items<32>(p, second, third, stream, prof_kind);
+        case 1: return launch_items<1>(p, stream, prof_kind);
+        case 2: return launch_items<2>(p, stream, prof_kind);
+        case 3: return launch_items<3>(p, stream, prof_kind);
+        case 4: return launch_items<4>(p, stream, prof_kind);
+        case 5: return launch_items<5>(p, stream, prof_kind);
+        case 6: return launch_items<6>(p, stream, prof_kind);
+        case 7: case 8: return launch_items<8>(p, stream, prof_kind);
+        case 9: case 10: return launch_items<10>(p, stream, prof_kind);
+        case 11: case 12: return launch_items<12>(p, stream, prof_kind);
+        case 13: case 14: return launch_items<14>(p, stream, prof_kind);
+        case 15: case 16: return launch_items<16>(p, stream, prof_kind);
+        case 17: case 18: return launch_items<18>(p, stream, prof_kind);
+        case 19: case 20: return launch_items<20>(p, stream, prof_kind);
+        case 21: case 22: case 23: case 24: return launch_items<24>(p, stream, prof_kind);
+        case 25: case 26: case 27: case 28: return launch_items<28>(p, stream, prof_kind);
+        default: return launch_items<32>(p, stream, prof_kind);
     }
 }
 

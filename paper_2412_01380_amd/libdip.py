@@ -119,6 +119,13 @@ def _load() -> C.CDLL:
     L.dip_swiglu_mlp_forward_batched.restype = i32
     L.dip_swiglu_mlp_forward_batched.argtypes = [C.POINTER(_Mlp), vp, i32, i32, i32, C.POINTER(_Cache),
                                                  C.POINTER(_Cache), f32, vp, vp, vp, vp, vp, sz, vp]
+    L.dip_swiglu_mlp_forward_batched_stack_workspace_bytes.restype = sz
+    L.dip_swiglu_mlp_forward_batched_stack_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32, i32, C.POINTER(i32),
+                                                                       C.POINTER(i32)]
+    L.dip_swiglu_mlp_forward_batched_stack.restype = i32
+    L.dip_swiglu_mlp_forward_batched_stack.argtypes = [C.POINTER(_Mlp), i32, vp, i64, i32, C.POINTER(i32),
+                                                       C.POINTER(i32), C.POINTER(_Cache), C.POINTER(_Cache), f32,
+                                                       vp, i64, vp, sz, vp]
     L.dip_glu_pruning_forward_workspace_bytes.restype = sz
     L.dip_glu_pruning_forward_workspace_bytes.argtypes = [C.POINTER(_Mlp), i32]
     L.dip_glu_pruning_forward.restype = i32
@@ -166,7 +173,8 @@ EXPORTS = ["dip_version", "dip_last_error", "dip_ca_scores", "dip_prune_topk", "
            "dip_swiglu_mlp_forward_workspace_bytes", "dip_swiglu_mlp_forward",
            "dip_swiglu_mlp_forward_noalloc", "dip_swiglu_mlp_forward_stack",
            "dip_swiglu_mlp_forward_stack_workspace_bytes", "dip_swiglu_mlp_forward_batched_workspace_bytes",
-           "dip_swiglu_mlp_forward_batched", "dip_glu_pruning_forward_workspace_bytes",
+           "dip_swiglu_mlp_forward_batched", "dip_swiglu_mlp_forward_batched_stack_workspace_bytes",
+           "dip_swiglu_mlp_forward_batched_stack", "dip_glu_pruning_forward_workspace_bytes",
            "dip_glu_pruning_forward", "dip_gathered_rowdot",
            "dip_partial_pruning_forward_workspace_bytes", "dip_partial_pruning_forward", "dip_tier_init_workspace_bytes",
            "dip_tier_init", "dip_tiered_mlp_forward_workspace_bytes", "dip_tiered_mlp_forward", "dip_tune_gemv", "dip_gemv_launch_shape", "dip_set_fusion", "dip_fused_launch_shape", "dip_stream_read", "dip_profile_enable", "dip_profile_read",
@@ -487,6 +495,22 @@ def dip_swiglu_mlp_forward_batched(mlp: Mlp, X, batch: int, k_in: int, k_mid: in
         C.byref(cache_mid.c) if cache_mid is not None else None,
         gamma, _ptr(Y, torch.float32), _ptr(mask_in_out, torch.int32), _ptr(h_out, torch.float32),
         _ptr(mask_mid_out, torch.int32), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def dip_swiglu_mlp_forward_batched_stack_workspace_bytes(stack: MlpStack, batch: int, k_in, k_mid) -> int:
+    return lib.dip_swiglu_mlp_forward_batched_stack_workspace_bytes(stack.mlps, stack.n, batch, _k_array(k_in, stack.n),
+                                                                    _k_array(k_mid, stack.n))
+
+
+def dip_swiglu_mlp_forward_batched_stack(stack: MlpStack, X, x_stride: int, batch: int, k_in, k_mid, gamma: float,
+                                         Y, y_stride: int, ws, stream=None) -> None:
+    """X: [n_layers][batch][d_model] (layer stride x_stride floats), Y likewise; k as in the stack call."""
+    import torch
+    ki = k_in if isinstance(k_in, C.Array) else _k_array(k_in, stack.n)
+    km = k_mid if isinstance(k_mid, C.Array) else _k_array(k_mid, stack.n)
+    _check(lib.dip_swiglu_mlp_forward_batched_stack(
+        stack.mlps, stack.n, _ptr(X, torch.float32), x_stride, batch, ki, km, stack.cin, stack.cmid, gamma,
+        _ptr(Y, torch.float32), y_stride, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def dip_glu_pruning_forward_workspace_bytes(mlp: Mlp, k: int) -> int:

@@ -155,3 +155,36 @@ def test_batched_config5_shape_batch_4(D):
     """B = 4 at the Phi-3-Medium int4 shape (the batch sizes 1, 2 and 8 are covered above)."""
     cfg = CONFIGS[5]
     run_steps(D, cfg.d_model, cfg.d_ff, "int4", 4, cfg.k_in(0.3), cfg.k_mid(0.3), steps=2, use_cache=True, seed=39)
+
+
+@pytest.mark.parametrize("fmt,B", [("bf16", 2), ("int4", 4)])
+def test_batched_stack_call_equals_per_layer_calls(D, fmt, B):
+    """The batched forward over a stack in one call (cache updates of all layers in one launch
+    at the end) against one batched call per layer: outputs and cache states bit-equal."""
+    d, L = 512, 3
+    ffs, k_in, k_mids = [1536, 2304, 1024], 150, [400, 700, 256]
+    mlps, ws_one = [], []
+    for l in range(L):
+        w = layer_weights(d, ffs[l], seed=61, layer=l, dtype=fmt)
+        mlps.append(D.Mlp(make_weight(D, w["ug"]), make_weight(D, w["d"])))
+        ws_one.append(workspace(D.dip_swiglu_mlp_forward_batched_workspace_bytes(mlps[l], B, k_in, k_mids[l])))
+    caches = [[D.Cache(d, 200) for _ in range(L)], [D.Cache(ffs[l], ffs[l] // 2) for l in range(L)],
+              [D.Cache(d, 200) for _ in range(L)], [D.Cache(ffs[l], ffs[l] // 2) for l in range(L)]]
+    for cs in caches:
+        for c in cs:
+            D.dip_cache_init(c)
+    stack = D.MlpStack(mlps, caches[0], caches[1])
+    ws = workspace(D.dip_swiglu_mlp_forward_batched_stack_workspace_bytes(stack, B, k_in, k_mids))
+    Y = torch.empty(L, B, d, dtype=torch.float32, device="cuda")
+    Y1 = torch.empty(B, d, dtype=torch.float32, device="cuda")
+    for t in range(3):
+        X = dev_f32(np.stack([ar1_laplace_stream(t + 1, d, seed=600 + l * 8 + b)[t] for l in range(L) for b in range(B)])
+                    .reshape(L, B, d))
+        D.dip_swiglu_mlp_forward_batched_stack(stack, X, B * d, B, k_in, k_mids, 0.2, Y, B * d, ws)
+        for l in range(L):
+            D.dip_swiglu_mlp_forward_batched(mlps[l], X[l], B, k_in, k_mids[l], caches[2][l], caches[3][l], 0.2, Y1,
+                                             None, None, None, ws_one[l])
+            torch.cuda.synchronize()
+            assert torch.equal(Y[l].view(torch.int32), Y1.view(torch.int32)), (t, l, "y")
+            for a, b in ((caches[0][l], caches[2][l]), (caches[1][l], caches[3][l])):
+                assert torch.equal(a.bits, b.bits) and torch.equal(a.stamp, b.stamp) and torch.equal(a.meta, b.meta), (t, l)
