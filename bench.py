@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+VALU_PEAK_TFLOPS = 157.3  # fp32 vector: 256 compute units x 128 FMA lanes x 2 flops x 2.4 GHz
 
 
 def parse():
@@ -366,6 +367,7 @@ def timed_repeats(one_block, blocks, repeats, min_repeat_ms):
     comes out shorter than the minimum (the pilot block ran slower than the steady state) has its
     block count raised and the whole set is measured again, so every reported repeat lasts at
     least `min_repeat_ms`.  Returns (blocks, [seconds per repeat])."""
+    import torch
     for _ in range(4):
         times = []
         for _ in range(max(1, repeats)):
@@ -787,6 +789,33 @@ def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gam
     ug_ms, ug_n = prof["gemv_upgate"]
     dn_ms, dn_n = prof["gemv_down"]
     ach = ug_bytes / (ug_ms / ug_n * 1e-3) / 1e9
+
+    # Which roofline binds a batched product: HBM on the bytes of the union, or the plain vector
+    # ALU on the arithmetic every stored code costs -- B multiply-adds (2 B flops) plus about 3
+    # operations to unpack it -- against 157.3 TFLOP/s (256 compute units x 4 x 64-lane fp32 FMA
+    # per 4 cycles x 2.4 GHz).  From 3 rows on the multiply-adds of int4 weights run on the matrix
+    # cores, the unpacking stays on the vector ALU; the vector-ALU model is quoted for every B.
+    def two_bounds(n_cols, codes_per_col, nbytes, us):
+        ops = n_cols * codes_per_col * (2 * B + 3)
+        t_hbm, t_alu = nbytes / (HBM_PEAK_GBS * 1e9), ops / (VALU_PEAK_TFLOPS * 1e12)
+        hbm = {"achieved_GBps": nbytes / (us * 1e-6) / 1e9, "peak_GBps": HBM_PEAK_GBS,
+               "frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "model_us": t_hbm * 1e6}
+        alu = {"achieved_TFLOPs": ops / (us * 1e-6) / 1e12, "peak_TFLOPs": VALU_PEAK_TFLOPS,
+               "frac": ops / (us * 1e-6) / 1e12 / VALU_PEAK_TFLOPS, "model_us": t_alu * 1e6, "ops_per_launch": ops}
+        return ("alu" if t_alu > t_hbm else "hbm"), hbm, alu
+    ug_us, dn_us = ug_ms / ug_n * 1e3, dn_ms / dn_n * 1e3
+    ug_bound, ug_hbm, ug_alu = two_bounds(u_in, 2 * f, ug_bytes, ug_us)
+    dn_bound, dn_hbm, dn_alu = two_bounds(u_mid, d, dn_bytes, dn_us)
+
+    def roof(bound, hbm, alu, **extra):
+        o = ({"bound": "alu", "achieved": alu["achieved_TFLOPs"], "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+              "frac": alu["frac"]} if bound == "alu" else
+             {"bound": "hbm", "achieved": hbm["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "frac": hbm["frac"]})
+        o.update({"traffic": None, "hbm": hbm, "alu": alu,
+                  "binds": f"{bound} (model: {hbm['model_us']:.1f} us of HBM, {alu['model_us']:.1f} us of vector ALU)"})
+        o.update(extra)
+        return o
     out = {
         "metric": "DIP MLP decode tokens/s at batch 1 + achieved HBM GB/s vs peak on gathered bytes",
         "value": B * 1e3 / ms_per_step, "unit": "row-layers/s (rows x layer-steps per second)",
@@ -809,12 +838,12 @@ def bench_batched(a, D, cfg, mlps, host0, X, Xd, cins, cmids, L, B, r, frac, gam
         "end_to_end_GBps": gathered / (ms_per_step * 1e-3) / 1e9,
         "setup_s": t_setup,
         "kernels_us": {k: (v[0] / v[1] * 1e3 if v[1] else None) for k, v in prof.items()},
-        "roofline": {"bound": "hbm" if B <= 2 else "mfma", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": ach / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "batched gathered product (up/gate), bytes of the measured union",
-                     "algorithmic_bytes_per_launch": ug_bytes, "avg_launch_us": ug_ms / ug_n * 1e3, "launches": ug_n},
-        "roofline_down": {"achieved": dn_bytes / (dn_ms / dn_n * 1e-3) / 1e9, "algorithmic_bytes_per_launch": dn_bytes,
-                          "avg_launch_us": dn_ms / dn_n * 1e3},
+        "roofline": roof(ug_bound, ug_hbm, ug_alu,
+                         kernel="batched gathered product (up/gate), bytes and codes of the measured union",
+                         algorithmic_bytes_per_launch=ug_bytes, avg_launch_us=ug_us, launches=ug_n),
+        "roofline_down": roof(dn_bound, dn_hbm, dn_alu,
+                              kernel="batched gathered product (down), bytes and codes of the measured union",
+                              algorithmic_bytes_per_launch=dn_bytes, avg_launch_us=dn_us, launches=dn_n),
     }
     print(json.dumps(out))
 
