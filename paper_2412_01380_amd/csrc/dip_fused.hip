@@ -40,6 +40,8 @@ struct HeadShared {
     uint32_t wave_tot[2][kWaves];
     float wave_max[kWaves];
     uint32_t bcast[4];
+    uint32_t cand[kNearCand];        // keys of the threshold bin
+    uint32_t ncand;
 };
 constexpr int kHeadHistWords = kBinsA + kBinsB + kBinsC;
 
@@ -177,35 +179,38 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
     for (int b = 0; b < kHeadHistWords / (2 * kSelThreads); ++b)
         reinterpret_cast<uint2*>(hs.hist)[b * kSelThreads + tid] = make_uint2(0u, 0u);
     hs.cw[tid] = (q.score_bits && tid < nwords) ? q.score_bits[tid] : 0u;
+    {
+        // ||v||_inf: the denominator of Eq. 10, and the anchor of the selection's histogram
+        float vmax = 0.f;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) vmax = fmaxf(vmax, fabsf(v[j]));
+        // (fmaxf drops a NaN operand: non-finite inputs leave M finite or infinite, never NaN)
+        vmax = wave_max_nonneg(vmax);
+        if (lane == 0) hs.wave_max[wave] = vmax;
+    }
     __syncthreads();
+    static_assert(kWaves == 16, "one wavefront maximum per lane of a 16-lane row");
+    const float M = row_max_nonneg(hs.wave_max[lane & (kWaves - 1)]);
 
-    // p = |v| for resident columns, fl(|v| * gamma) for the others (plain DIP: p = |v|)
-    float vmax = 0.f;
+    // p = |v| for resident columns, fl(|v| * gamma) for the others (plain DIP: p = |v|); p <= M
     if (q.score_bits) {
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
             const float a = fabsf(v[j]);
-            vmax = fmaxf(vmax, a);
             const uint32_t c = (hs.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u;
             key[j] = __float_as_uint(c ? a : __fmul_rn(a, q.gamma)) << 1;
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, off));
-        if (lane == 0) hs.wave_max[wave] = vmax;   // read after the first barrier of the select
     } else {
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) key[j] = __float_as_uint(fabsf(v[j])) << 1;
     }
 
     uint32_t Tk, need;
-    block_select_largest<ITEMS, false>(key, (uint32_t)p.k, hs, phase, Tk, need, true);
+    block_select_largest_near_max<ITEMS>(key, __float_as_uint(M) << 1, (uint32_t)p.k, hs, phase, Tk, need);
 
     // keys in [K_lo, K_hi) tie at the k-th largest score, keys >= K_hi lie above it
     uint32_t K_lo = Tk, K_hi = Tk + 1u;
-    float M = 0.f;
     if (q.score_bits) {
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, hs.wave_max[w]);
         if (M > 0.f) {
             const uint32_t Tb = Tk >> 1;
             const float Ts = __fdiv_rn(__uint_as_float(Tb), M);

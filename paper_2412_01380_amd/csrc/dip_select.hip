@@ -47,6 +47,8 @@ struct SelShared {
     float wave_max[kWaves];
     uint32_t bcast[4];
     uint32_t cnt[8];
+    uint32_t cand[kNearCand];        // keys of the threshold bin
+    uint32_t ncand;
 };
 
 __device__ __forceinline__ void store_ballot_words(uint32_t* words, int nwords, int first_word,
@@ -136,17 +138,17 @@ __device__ __forceinline__ void select_body(SelectParams& p, SelShared& sh) {
 
     if (!p.mask_in) {
         // ---- Alg. 1 step 1: scores --------------------------------------------------
-        float M = 0.f;
-        if (p.score_bits || p.rowmax_out) {
+        // ||v||_inf: the denominator of Eq. 10, and the anchor of the selection's histogram
+        float M;
+        {
             float m = 0.f;
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) m = fmaxf(m, fabsf(v[j]));
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            m = wave_max_nonneg(m);
             if (lane == 0) sh.wave_max[wave] = m;
             __syncthreads();
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sh.wave_max[w]);
+            static_assert(kWaves == 16, "one wavefront maximum per lane of a 16-lane row");
+            M = row_max_nonneg(sh.wave_max[lane & (kWaves - 1)]);
             if (p.rowmax_out && tid == 0) p.rowmax_out[0] = __float_as_uint(M);
         }
         if (p.score_bits) {
@@ -176,7 +178,9 @@ __device__ __forceinline__ void select_body(SelectParams& p, SelShared& sh) {
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) key[j] <<= 1;
         uint32_t T, need, n_equal;
-        block_select_largest<ITEMS, false>(key, (uint32_t)p.k, sh, phase, T, need, true, &n_equal);
+        // no key exceeds the score 1 (Eq. 10 divides by the maximum) or, without a cache, M
+        const uint32_t max_key = (p.score_bits ? (M > 0.f ? __float_as_uint(1.0f) : 0u) : __float_as_uint(M)) << 1;
+        block_select_largest_near_max<ITEMS>(key, max_key, (uint32_t)p.k, sh, phase, T, need, &n_equal);
         const bool want_words = p.mask_out || p.c_bits;
         // a wave ballot over slot j is two words of the mask: lane 2j keeps the low word and
         // lane 2j+1 the high word, stored to LDS once after the loop

@@ -37,6 +37,29 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
     return (uint32_t)v;
 }
 
+// Maximum of a non-negative float over the lanes of a wavefront, with data-parallel
+// primitives (non-negative floats order as their bit patterns; a lane without a source keeps
+// 0).  wave_max_nonneg: all 64 lanes; row_max_nonneg: the 16 lanes of the caller's row.
+// Every lane receives the result.
+__device__ __forceinline__ float row_max_nonneg(float x) {
+    int v = __float_as_int(x);
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false));  // row_shr:1
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false));  // row_shr:2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false));  // row_shr:4
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false));  // row_shr:8
+    return __int_as_float(__builtin_amdgcn_readlane(v, 15));
+}
+__device__ __forceinline__ float wave_max_nonneg(float x) {
+    int v = __float_as_int(x);
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false));  // row_shr:1
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false));  // row_shr:2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false));  // row_shr:4
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false));  // row_shr:8
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));  // row_bcast:15 -> rows 1, 3
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));  // row_bcast:31 -> rows 2, 3
+    return __int_as_float(__builtin_amdgcn_readlane(v, 63));
+}
+
 // Exclusive prefix sum over the 1024 lanes of the workgroup (one barrier).  `phase`
 // alternates between two LDS buffers so that back-to-back calls need no trailing barrier.
 template <typename SH>
@@ -220,6 +243,97 @@ __device__ __forceinline__ void hist_add_callers(uint32_t* hist, uint32_t d) {
     } else {
         atomicAdd(&hist[d], 1u);
     }
+}
+
+// The k-th largest key and its tie count as block_select_largest returns them, for keys that
+// are bit patterns of non-negative floats (shifted left by one) and `max_key` >= every key,
+// found with ONE histogram pass in the usual case.
+//
+// The first generic digit is sign, exponent and three mantissa bits: 16 bins per octave, the
+// threshold bin holds a few per cent of the keys, and two more passes over all keys must
+// refine it.  Here the bins are laid from the maximum downwards, 512 per octave over eight
+// octaves (bin 4095 - ((max_key - key) >> 15); keys farther down are not counted): the
+// threshold bin then holds about a thousandth of the keys.  Those are copied to a short list
+// in LDS, and every wavefront ranks the list in registers -- no further pass, no further bin
+// search.  When the k-th largest key is not within eight octaves of the maximum, or its bin
+// holds more than kNearCand keys (many equal values), the generic digits are run instead.
+// SH needs cand[kNearCand] and ncand besides the fields block_select_largest uses.
+// Requires k >= 1 and sh.hist all zero behind a barrier.  `n_equal` (nullable): the number of
+// keys equal to T.
+constexpr int kNearCand = 64;
+
+template <int ITEMS, typename SH>
+__device__ __forceinline__ void block_select_largest_near_max(const uint32_t (&key)[ITEMS],
+                                                              uint32_t max_key, uint32_t k, SH& sh,
+                                                              int& phase, uint32_t& T, uint32_t& need,
+                                                              uint32_t* n_equal = nullptr) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t* histA = sh.hist;
+    constexpr uint32_t kShift = 15;
+    constexpr uint32_t kRange = (uint32_t)(kBinsA - 1) << kShift;   // bins 1..4095; bin 0 stays empty
+    constexpr uint32_t kNone = 0xffffffffu;
+    if (max_key == 0u) {        // every key is 0: they all tie (uniform over the workgroup)
+        T = 0u;
+        need = k;
+        if (n_equal) *n_equal = (uint32_t)(ITEMS * kSelThreads);
+        return;
+    }
+    if (tid == 0) {
+        sh.bcast[0] = kNone;    // stays if the bins hold fewer than k keys
+        sh.ncand = 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const uint32_t d = max_key - key[j];     // (a key above max_key -- a NaN -- wraps to "far")
+        if (d < kRange) atomicAdd(&histA[(uint32_t)(kBinsA - 1) - (d >> kShift)], 1u);
+    }
+    __syncthreads();
+    uint32_t b1, above, inbin;
+    find_bin<kBinsA / kSelThreads>(histA, k, sh, phase, b1, above, inbin);
+    // (read from LDS by every lane: the same everywhere; say so to the compiler)
+    b1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)b1);
+    above = (uint32_t)__builtin_amdgcn_readfirstlane((int)above);
+    inbin = (uint32_t)__builtin_amdgcn_readfirstlane((int)inbin);
+    if (b1 == kNone || inbin > (uint32_t)kNearCand) {
+        // not near the maximum, or a crowd of equal keys
+        for (int b = tid; b < kBinsA; b += kSelThreads) histA[b] = 0u;
+        __syncthreads();
+        block_select_largest<ITEMS, false>(key, k, sh, phase, T, need, true, n_equal);
+        return;
+    }
+    const uint32_t remaining = k - above;        // 1 <= remaining <= inbin
+    // the keys of the threshold bin: max_key - key in [q << kShift, (q + 1) << kShift)
+    const uint32_t top = max_key - (((uint32_t)(kBinsA - 1) - b1) << kShift);
+    // (a lane holds one only rarely: the distance of its nearest key below `top` decides with
+    //  two instructions per key whether the lane looks at its keys one by one)
+    uint32_t nearest = 0xffffffffu;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) nearest = min(nearest, top - key[j]);
+    if (nearest < (1u << kShift)) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (top - key[j] < (1u << kShift)) {
+                const uint32_t at = atomicAdd(&sh.ncand, 1u);
+                if (at < (uint32_t)kNearCand) sh.cand[at] = key[j];
+            }
+        }
+    }
+    __syncthreads();
+    // every wavefront ranks the candidates by itself: lane l holds candidate l and counts the
+    // candidates above it and not below it
+    const uint32_t c = lane < (int)inbin ? sh.cand[lane] : 0u;
+    uint32_t gt = 0u, ge = 0u;
+    for (uint32_t j = 0; j < inbin; ++j) {
+        const uint32_t cj = (uint32_t)__builtin_amdgcn_readlane((int)c, (int)j);
+        gt += cj > c ? 1u : 0u;
+        ge += cj >= c ? 1u : 0u;
+    }
+    const uint64_t at_threshold = __ballot(lane < (int)inbin && gt < remaining && remaining <= ge);
+    const int lt = at_threshold ? __builtin_ctzll(at_threshold) : 0;
+    T = (uint32_t)__builtin_amdgcn_readlane((int)c, lt);
+    const uint32_t gt_t = (uint32_t)__builtin_amdgcn_readlane((int)gt, lt);
+    need = remaining - gt_t;
+    if (n_equal) *n_equal = (uint32_t)__builtin_amdgcn_readlane((int)ge, lt) - gt_t;
 }
 
 // The same selection over a list of `count` keys in LDS; lane `tid` owns the entries
