@@ -125,6 +125,37 @@ struct ListGe {
     }
 };
 
+// Mask words of the selection, slot by slot (a template recursion: the lane numbers are constants).
+template <int J, int ITEMS>
+struct MaskWords {
+    __device__ static __forceinline__ void run(const uint32_t (&key)[ITEMS], uint32_t K_lo, uint32_t K_hi, bool fast,
+                                               uint32_t take, uint32_t eq_seen, int next, int G, int& my_word) {
+        // `next`: the next slot of this workgroup (g, g + G, ...; uniform, and no division)
+        if (J == next) {
+            slot(key, K_lo, K_hi, fast, take, eq_seen, my_word);
+            next += G;
+        }
+        if constexpr (J + 1 < ITEMS) MaskWords<J + 1, ITEMS>::run(key, K_lo, K_hi, fast, take, eq_seen, next, G, my_word);
+    }
+    __device__ static __forceinline__ void slot(const uint32_t (&key)[ITEMS], uint32_t K_lo, uint32_t K_hi, bool fast,
+                                                uint32_t take, uint32_t eq_seen, int& my_word) {
+        bool mine;
+        if (fast) {
+            mine = key[J] >= K_lo;
+        } else {
+            // ties at the threshold: the `take` lowest indices among them are selected
+            mine = key[J] >= K_hi;
+            const bool tie = key[J] >= K_lo && !mine;
+            const uint64_t be = __ballot(tie);
+            const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)eq_seen, J) & 0xffffu;
+            mine = mine || (tie && eq_before + lanes_below(be) < take);
+        }
+        const uint64_t bs = __ballot(mine);
+        write_lane<(2 * J) & 63>(my_word, (uint32_t)bs);
+        write_lane<(2 * J + 1) & 63>(my_word, (uint32_t)(bs >> 32));
+    }
+};
+
 template <typename WT, int LPR, int NSEG>
 struct FusedShared {
     typedef Tile<WT, LPR, kFusedWaves, 4, NSEG> T;
@@ -134,6 +165,7 @@ struct FusedShared {
         HeadShared head;                              // selection
         float red[kFusedWaves][NSEG][T::SC];          // reduction across wavefronts
     } u;
+    uint32_t mwords[kMaxWords];      // mask words on their way out (the workgroup that writes them)
     int s_last;
 };
 
@@ -151,7 +183,10 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
     const int kb = min(p.k, g * p.rows_per_split);   // rows_per_split is a multiple of 8, <= kFusedListCap
     const int ke = min(p.k, kb + p.rows_per_split);
     // the workgroup that also writes the launch-wide outputs of the selection
+    // ... of the scores (workgroup (0, 0)) and of the mask words (the workgroups of strip 0 take
+    // the slots in turn: slot j belongs to the workgroup with g == j mod G)
     const bool scribe = strip == 0 && g == 0;
+    const bool mask_scribe = strip == 0 && q.mask_out != nullptr;
     const int nwords = (q.n + 31) >> 5;
     int phase = 0;
 
@@ -283,7 +318,7 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
         __syncthreads();
         for (int t = tid; t < ke - kb; t += kSelThreads) q.idx_out[kb + t] = sh.l_idx[t];
     }
-    if (scribe && q.mask_out) {
+    if (mask_scribe) {
         uint32_t take = 0u, eq_seen = 0u;
         if (!fast) {
             // recount: how many ties are selected, and how many ties precede each tile
@@ -292,22 +327,15 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
             take = (uint32_t)p.k > (totals >> 16) ? (uint32_t)p.k - (totals >> 16) : 0u;
             eq_seen = (uint32_t)pre;
         }
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            bool mine = key[j] >= K_hi;
-            if (!fast) {
-                const bool tie = key[j] >= K_lo && !mine;
-                const uint64_t be = __ballot(tie);
-                const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)eq_seen, j) & 0xffffu;
-                mine = mine || (tie && eq_before + lanes_below(be) < take);
-            } else {
-                mine = key[j] >= K_lo;
-            }
-            const uint64_t bs = __ballot(mine);
-            const int w0 = j * (kSelThreads / 32) + wave * 2;
-            if (lane == 0 && w0 < nwords) q.mask_out[w0] = (uint32_t)bs;
-            if (lane == 32 && w0 + 1 < nwords) q.mask_out[w0 + 1] = (uint32_t)(bs >> 32);
-        }
+        // A wave ballot over slot j is two words of the mask: lane 2j keeps the low word and
+        // lane 2j+1 the high word, and the words go to LDS once after the loop, to memory one
+        // per lane behind the barrier below.  (A workgroup barrier waits for the stores issued
+        // before it: stores from inside the loop would hold this workgroup back by
+        // microseconds, and with it the launch, which ends with its slowest workgroup.)
+        int my_word = 0;
+        MaskWords<0, ITEMS>::run(key, K_lo, K_hi, fast, take, eq_seen, g, G, my_word);
+        if (lane < 2 * ITEMS)
+            sh.mwords[((lane >> 1) * (kSelThreads / 32) + wave * 2 + (lane & 1)) & (kMaxWords - 1)] = (uint32_t)my_word;
     }
     if (scribe && q.s_out) {
         // the scores themselves, for stage-wise comparison: Eq. 10 in its stated operation order
@@ -319,6 +347,11 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
         }
     }
     __syncthreads();   // the list is complete; the selection's LDS may be reused
+    if (mask_scribe) {
+        // the 32 words of this workgroup's slots g, g + G, ...: 32 lanes per slot
+        const int slot = g + (tid >> 5) * G, w = slot * (kSelThreads / 32) + (tid & 31);
+        if (slot < ITEMS && w < nwords) q.mask_out[w] = sh.mwords[w & (kMaxWords - 1)];
+    }
 
     // ---- body and tail: Alg. 1 step 4 on this workgroup's share ---------------------------------
     float acc[NSEG][T::EPL];

@@ -137,6 +137,24 @@ def _adversarial_inputs(d, rng):
     x[::2] = np.nextafter(np.float32(2.0), np.float32(3.0))          # two neighbouring floats
     x[3] = 7.0
     out["neighbouring floats"] = x
+    # The one-pass selection ranks the keys of the threshold bin (2^14 consecutive bit patterns,
+    # counted down from the maximum) in registers when there are at most 64 of them and runs
+    # the generic digits otherwise: m distinct keys in one such bin around the (d // 3)-th
+    # largest, for m on both sides of 64 and with a pair of equal keys among them.
+    top = np.float32(2.0).view(np.uint32)
+    for m in (1, 63, 64, 65, 90):
+        bits = np.empty(d, dtype=np.uint32)
+        n_above = d // 3 - m // 2
+        bits[:n_above] = top - rng.integers(1 << 14, 40 << 14, size=n_above).astype(np.uint32)
+        bits[n_above:n_above + m] = top - np.uint32(50 << 14) - 1 - rng.permutation(m).astype(np.uint32)
+        if m > 2:
+            bits[n_above + 1] = bits[n_above]                    # a tie inside the bin
+        rest = d - n_above - m
+        bits[n_above + m:] = (rng.random(rest).astype(np.float32) * np.float32(1e-6)).view(np.uint32)
+        bits[0] = top
+        x = bits.view(np.float32).copy()
+        x *= rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=d)
+        out[f"threshold bin of {m}"] = x[rng.permutation(d)]
     return out
 
 

@@ -101,6 +101,36 @@ def test_topk_tie_storms(D, n):
                 _check_topk(D, s, k)
 
 
+@pytest.mark.parametrize("n", [520, 5120, 17920])
+def test_topk_threshold_bin_sizes_and_far_thresholds(D, n):
+    """The selection counts the keys in bins laid down from the maximum, ranks the keys of the
+    threshold bin in registers when they are at most 64, and falls back to generic radix digits
+    when they are more or when the k-th largest key lies more than eight octaves below the
+    maximum: bins of 1, 63, 64, 65 and 200 distinct keys (with one tie), and thresholds 2^-9,
+    2^-30 and 2^-120 of the maximum."""
+    rng = np.random.default_rng(n)
+    top = np.float32(2.0).view(np.uint32)
+    k = n // 3
+    for m in (1, 63, 64, 65, 200):
+        bits = np.empty(n, dtype=np.uint32)
+        n_above = k - m // 2
+        bits[:n_above] = top - rng.integers(1 << 14, 40 << 14, size=n_above).astype(np.uint32)
+        bits[n_above:n_above + m] = top - np.uint32(50 << 14) - 1 - rng.permutation(m).astype(np.uint32)
+        if m > 2:
+            bits[n_above + 1] = bits[n_above]
+        bits[n_above + m:] = (rng.random(n - n_above - m).astype(np.float32) * np.float32(1e-6)).view(np.uint32)
+        bits[0] = top
+        s = bits.view(np.float32)[rng.permutation(n)].copy()
+        for kk in (k - m // 2 - 1, k - 1, k, k + 1, min(n, k + m)):
+            if kk >= 1:
+                _check_topk(D, s, kk)
+    for scale in (2.0 ** -9, 2.0 ** -30, 2.0 ** -120):
+        s = (rng.random(n).astype(np.float32) + np.float32(0.5)) * np.float32(scale)
+        s[rng.choice(n, size=5, replace=False)] = np.float32(3.0)
+        for kk in (1, 5, 6, k, n):
+            _check_topk(D, s, kk)
+
+
 def test_topk_single_output_forms(D):
     n, k = 1000, 300
     s = np.abs(studentt_tokens(1, n, seed=7)[0])
