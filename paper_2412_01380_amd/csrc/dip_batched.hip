@@ -18,6 +18,7 @@
 //                    (SwiGLU for the bundled up/gate matrix, Sec. 3 Eq. 2)
 
 #include "dip_internal.h"
+#include "dip_select_device.h"
 
 namespace dip {
 namespace {
@@ -33,31 +34,51 @@ constexpr int kUnionWordsPerWg = kUnionThreads / 32;   // one lane per feature o
 // Every workgroup scans the popcounts of all union words (two words per thread, at most 1024
 // words), which gives each word the number of listed indices before it; it then lists the
 // features of its own 16 words, one lane per feature, so the reads of x are coalesced.
+// Everything a lane will need -- the words it counts, the word of its own feature in every
+// row and the feature's activations -- is requested before anything is waited for: the kernel
+// is one memory round trip, a scan and the stores.
 __global__ __launch_bounds__(kUnionThreads) void union_kernel(UnionParams p) {
     __shared__ uint32_t s_base[2 * kUnionThreads];
     __shared__ uint32_t s_wave[kUnionThreads / 64];
+    constexpr int kMaxBatch = 8;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int B = p.batch;
     const int nwords = (p.n + 31) >> 5;
     const int w0 = 2 * tid, w1 = 2 * tid + 1;
-    uint32_t u0 = 0, u1 = 0;
-    for (int b = 0; b < p.batch; ++b) {
-        if (w0 < nwords) u0 |= p.masks[(size_t)b * p.words_stride + w0];
-        if (w1 < nwords) u1 |= p.masks[(size_t)b * p.words_stride + w1];
-    }
-    const uint32_t c0 = (uint32_t)__popc(u0), c1 = (uint32_t)__popc(u1);
-    uint32_t inc = c0 + c1;
+    const int w = blockIdx.x * kUnionWordsPerWg + (tid >> 5), bit = tid & 31;
+    // (reads past the end are redirected to the last word / feature and dropped)
+    const int w0c = min(w0, nwords - 1), w1c = min(w1, nwords - 1), wc = min(w, nwords - 1);
+    const int i = w * 32 + bit, ic = min(i, p.n - 1);
+    uint32_t a0[kMaxBatch], a1[kMaxBatch], mw[kMaxBatch];
+    float xv[kMaxBatch];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t t = __shfl_up(inc, off);
-        if (lane >= off) inc += t;
+    for (int b = 0; b < kMaxBatch; ++b) {
+        a0[b] = 0u; a1[b] = 0u; mw[b] = 0u; xv[b] = 0.f;
+        if (b < B) {    // (uniform)
+            const uint32_t* mrow = p.masks + (size_t)b * p.words_stride;
+            a0[b] = mrow[w0c];
+            a1[b] = mrow[w1c];
+            mw[b] = mrow[wc];
+            xv[b] = p.x[(size_t)b * p.x_stride + ic];
+        }
     }
+    uint32_t u0 = 0u, u1 = 0u;
+#pragma unroll
+    for (int b = 0; b < kMaxBatch; ++b) {
+        u0 |= a0[b];
+        u1 |= a1[b];
+    }
+    if (w0 >= nwords) u0 = 0u;
+    if (w1 >= nwords) u1 = 0u;
+    const uint32_t c0 = (uint32_t)__popc(u0), c1 = (uint32_t)__popc(u1);
+    const uint32_t inc = sel::wave_incl_scan(c0 + c1);
     if (lane == 63) s_wave[wave] = inc;
     __syncthreads();
     uint32_t before = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < kUnionThreads / 64; ++w) {
-        const uint32_t t = s_wave[w];
-        if (w < wave) before += t;
+    for (int ww = 0; ww < kUnionThreads / 64; ++ww) {
+        const uint32_t t = s_wave[ww];
+        if (ww < wave) before += t;
         total += t;
     }
     const uint32_t excl = before + inc - (c0 + c1);
@@ -70,20 +91,30 @@ __global__ __launch_bounds__(kUnionThreads) void union_kernel(UnionParams p) {
     }
     __syncthreads();
 
-    const int w = blockIdx.x * kUnionWordsPerWg + (tid >> 5), bit = tid & 31;
     if (w >= nwords) return;
     uint32_t rows = 0, uw = 0;    // bit b of rows: row b selected this feature
-    for (int b = 0; b < p.batch; ++b) {
-        const uint32_t m = p.masks[(size_t)b * p.words_stride + w];
-        uw |= m;
-        rows |= ((m >> bit) & 1u) << b;
+#pragma unroll
+    for (int b = 0; b < kMaxBatch; ++b) {
+        uw |= mw[b];
+        rows |= ((mw[b] >> bit) & 1u) << b;
     }
     if (!rows) return;
     const uint32_t pos = s_base[w] + (uint32_t)__popc(uw & ((1u << bit) - 1u));
-    const int i = w * 32 + bit;
     p.uidx[pos] = i;
-    for (int b = 0; b < p.batch; ++b)
-        p.uval[(size_t)pos * p.batch + b] = ((rows >> b) & 1u) ? p.x[(size_t)b * p.x_stride + i] : 0.f;
+    float m[kMaxBatch];
+#pragma unroll
+    for (int b = 0; b < kMaxBatch; ++b) m[b] = ((rows >> b) & 1u) ? xv[b] : 0.f;
+    float* dst = p.uval + (size_t)pos * B;
+    if (B == 8) {
+        reinterpret_cast<float4*>(dst)[0] = make_float4(m[0], m[1], m[2], m[3]);
+        reinterpret_cast<float4*>(dst)[1] = make_float4(m[4], m[5], m[6], m[7]);
+    } else if (B == 4) {
+        reinterpret_cast<float4*>(dst)[0] = make_float4(m[0], m[1], m[2], m[3]);
+    } else {
+#pragma unroll
+        for (int b = 0; b < kMaxBatch; ++b)
+            if (b < B) dst[b] = m[b];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -515,7 +546,8 @@ __global__ __launch_bounds__(kMWaves * 64) void bgemv_q4_mfma_kernel(BatchedGemv
 
 // out[b][j] = sum over shares of partial[g][b][j]   (glu == 0), or
 // out[b][j] = up * SiLU(gate), up = sum partial[g][b][j], gate = sum partial[g][b][half + j];
-// eight partial sums in flight at a time, added in share order
+// up to 20 shares in flight at a time (one or two memory round trips for the usual numbers
+// of shares), added in share order
 __global__ void breduce_kernel(BatchedReduceParams p) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int b = blockIdx.y;
@@ -524,16 +556,20 @@ __global__ void breduce_kernel(BatchedReduceParams p) {
     const size_t gstride = (size_t)p.batch * (size_t)p.n_out;
     const float* src = p.partial + (size_t)b * (size_t)p.n_out + j;
     float s0 = 0.f, s1 = 0.f;
-    for (int g0 = 0; g0 < p.shares; g0 += 8) {
-        float a8[8], b8[8];
+    // (loads past the last share re-read it and are dropped: a load under a branch would be
+    //  waited for where the branch ends, one round trip each)
+    constexpr int kInFlight = 20;
+    const size_t goff = p.glu ? (size_t)width : 0;
+    for (int g0 = 0; g0 < p.shares; g0 += kInFlight) {
+        float a8[kInFlight], b8[kInFlight];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < kInFlight; ++i) {
             const int gg = g0 + i < p.shares ? g0 + i : p.shares - 1;
             a8[i] = src[(size_t)gg * gstride];
-            b8[i] = p.glu ? src[(size_t)gg * gstride + width] : 0.f;
+            b8[i] = src[(size_t)gg * gstride + goff];
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < kInFlight; ++i)
             if (g0 + i < p.shares) { s0 += a8[i]; s1 += b8[i]; }
     }
     p.out[(size_t)b * p.out_stride + j] = p.glu ? s0 * (s1 / (1.0f + expf(-s1))) : s0;
