@@ -139,3 +139,62 @@ def test_tune_validation(D):
     assert D.lib.dip_tune_gemv(7, 0, 0, 0) == D.DIP_ERR_INVALID_ARG
     assert D.lib.dip_tune_gemv(0, 3, 0, 0) == D.DIP_ERR_INVALID_ARG
     assert D.lib.dip_tune_gemv(0, 0, 0, 0) == D.DIP_OK
+
+
+def test_one_cache_state_for_two_pruning_points_is_rejected(D):
+    """A cache is scored in one launch and updated at the end of the call: two pruning points (or
+    two layers) that share one state would read it while it changes.  Rejected on the host."""
+    from paper_2412_01380_amd.libdip import _Cache, _Mlp
+    L = D.lib
+    d = f = 64                                  # equal widths, so one state fits both points
+    mlp = _Mlp(_weight(D, 1, d, 2 * f), _weight(D, 1, f, d))
+    c = _Cache(FAKE, FAKE, FAKE, d, 32, 0, 0)
+    other = _Cache(FAKE + 4096, FAKE, FAKE, d, 32, 0, 0)
+    args = (C.byref(mlp), FAKE, 16, 16)
+    tail = (0.2, FAKE, None, FAKE, 1 << 24, None)
+    assert L.dip_swiglu_mlp_forward(*args, C.byref(c), C.byref(c), *tail) == D.DIP_ERR_INVALID_ARG
+    assert "share" in D.dip_last_error()
+    # the batched call applies the same rule
+    assert L.dip_swiglu_mlp_forward_batched(C.byref(mlp), FAKE, 2, 16, 16, C.byref(c), C.byref(c), 0.2, FAKE,
+                                            None, None, None, FAKE, 1 << 26, None) == D.DIP_ERR_INVALID_ARG
+    # two layers of a stack with the same state at point 1
+    mlps = (_Mlp * 2)(mlp, mlp)
+    cin = (_Cache * 2)(c, c)
+    cmid = (_Cache * 2)(other, _Cache(FAKE + 8192, FAKE, FAKE, d, 32, 0, 0))
+    k = (C.c_int32 * 2)(16, 16)
+    assert L.dip_swiglu_mlp_forward_stack(mlps, 2, FAKE, d, k, k, cin, cmid, 0.2, FAKE, d, FAKE, 1 << 26,
+                                          None) == D.DIP_ERR_INVALID_ARG
+
+
+def test_stack_and_no_alloc_argument_validation(D):
+    from paper_2412_01380_amd.libdip import _Mlp
+    L = D.lib
+    d, f = 64, 128
+    mlp = _Mlp(_weight(D, 1, d, 2 * f), _weight(D, 1, f, d))
+    mlps = (_Mlp * 2)(mlp, mlp)
+    k_in, k_mid = (C.c_int32 * 2)(16, 16), (C.c_int32 * 2)(32, 200)
+    # per-layer k: layer 1 asks for more than d_ff
+    assert L.dip_swiglu_mlp_forward_stack_workspace_bytes(mlps, 2, k_in, k_mid) == 0
+    assert L.dip_swiglu_mlp_forward_stack(mlps, 2, FAKE, d, k_in, k_mid, None, None, 0.2, FAKE, d, FAKE, 1 << 26,
+                                          None) == D.DIP_ERR_INVALID_ARG
+    k_mid = (C.c_int32 * 2)(32, 64)
+    need = L.dip_swiglu_mlp_forward_stack_workspace_bytes(mlps, 2, k_in, k_mid)
+    assert need > 0
+    assert L.dip_swiglu_mlp_forward_stack(mlps, 2, FAKE, d, k_in, k_mid, None, None, 0.2, FAKE, d, FAKE, need - 1,
+                                          None) == D.DIP_ERR_WORKSPACE
+    assert L.dip_swiglu_mlp_forward_stack(mlps, 0, FAKE, d, k_in, k_mid, None, None, 0.2, FAKE, d, FAKE, need,
+                                          None) == D.DIP_ERR_INVALID_ARG
+    assert L.dip_swiglu_mlp_forward_stack(mlps, 2, FAKE, d, None, k_mid, None, None, 0.2, FAKE, d, FAKE, need,
+                                          None) == D.DIP_ERR_INVALID_ARG
+    assert L.dip_swiglu_mlp_forward_batched_stack_workspace_bytes(mlps, 2, 9, k_in, k_mid) == 0      # batch > 8
+    assert L.dip_swiglu_mlp_forward_batched_stack(mlps, 2, FAKE, 8 * d, 9, k_in, k_mid, None, None, 0.2, FAKE,
+                                                  8 * d, FAKE, 1 << 26, None) == D.DIP_ERR_INVALID_ARG
+    # the entry point that allocates nothing: bad arguments and layers beyond its built-in buffer are
+    # turned away before the runtime is touched
+    assert L.dip_swiglu_mlp_forward_noalloc(C.byref(mlp), FAKE, 0, 32, None, None, 0.2, FAKE, None,
+                                            None) == D.DIP_ERR_INVALID_ARG
+    big = _Mlp(_weight(D, 0, 16384, 2 * 32768), _weight(D, 0, 32768, 16384))
+    assert L.dip_swiglu_mlp_forward_workspace_bytes(C.byref(big), 8192, 16384) + 2 * 4096 > D.DIP_STATIC_SCRATCH_BYTES
+    assert L.dip_swiglu_mlp_forward_noalloc(C.byref(big), FAKE, 8192, 16384, None, None, 0.2, FAKE, None,
+                                            None) == D.DIP_ERR_WORKSPACE
+    assert "built-in" in D.dip_last_error()
