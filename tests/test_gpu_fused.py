@@ -212,7 +212,8 @@ def _run_tokens(D, L, xs, k_in, k_mid, d, f):
 
 
 @pytest.mark.parametrize("d,f,fmt,lpr,ks", [(1024, 2048, "f32", 32, 3), (3072, 8192, "bf16", 32, 8),
-                                            (2048, 5120, "int4", 16, 4), (1032, 1160, "bf16", 64, 2)])
+                                            (2048, 5120, "int4", 16, 4), (1032, 1160, "bf16", 64, 2),
+                                            (5120, 17920, "bf16", 32, 3)])
 def test_one_launch_form_equals_two_launch_form_bit_for_bit(D, d, f, fmt, lpr, ks):
     k_in, k_mid = d // 2, f // 3
     D.dip_tune_gemv(lpr, 16, ks, 4)          # both forms, both products: one launch shape
