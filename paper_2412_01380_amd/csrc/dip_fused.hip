@@ -17,7 +17,7 @@
 // is monotone, so the k-th largest score is T_s = fl(T_p / M) with T_p the k-th largest p, and
 //     { s > T_s }  = { p >= P_hi },  P_hi = the smallest float with fl(P_hi / M) >  T_s
 //     { s == T_s } = { P_lo <= p < P_hi },  P_lo = the smallest float with fl(P_lo / M) >= T_s.
-// The radix select therefore runs on the bit patterns of p, and only P_lo and P_hi need
+// The selection therefore runs on the bit patterns of p, and only P_lo and P_hi need
 // divisions: 64 candidates around T_p, one per lane, settle them in one step (a bisection
 // over all floats covers the case that the window is too small, e.g. denormal scores).  The
 // selected set is then exactly the top-K of the rounded scores with lowest-index ties -- the

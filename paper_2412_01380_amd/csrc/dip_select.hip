@@ -9,17 +9,19 @@
 // ascending index order, which is what the lowest-index tie rule and the ascending
 // index list need.
 //
-// top-K is a most-significant-digit radix select (12 + 10 + 10 bits) on the 32-bit key
-// patterns; non-negative floats order like their bit patterns.  The first digit is
-// histogrammed from the registers; the two remaining digits only look at the keys that fall
-// into the threshold bin (a few per cent of the vector).  Eviction victims (smallest
-// (stamp, index) first) are the largest ages (current step - stamp) among the evictable
-// columns, found by the same radix select.
+// top-K works on the 32-bit key patterns (non-negative floats order like their bit patterns):
+// one histogram pass with bins laid from the largest possible key downwards, 512 per octave,
+// then the few keys of the threshold bin are ranked in registers
+// (block_select_largest_near_max); when the k-th largest key is not within eight octaves of
+// the maximum, or many keys share its bin, a most-significant-digit radix select (12 + 10 + 10
+// bits) takes over, whose two last digits only look at the keys of the threshold bin.
+// Eviction victims (smallest (stamp, index) first) are the largest ages (current step -
+// stamp) among the evictable columns, found by that radix select.
 //
 // The kernel runs on one compute unit and is bound by what that unit does in sequence: the
 // instructions per key (16 wavefronts share 4 SIMDs: every instruction executed per key costs
-// 16 cycles of the workgroup), the LDS adds of the first radix digit (the keys of an
-// activation vector crowd into a few dozen bins) and a dozen barrier-separated LDS round
+// 16 cycles of the workgroup), the LDS adds of the histogram (with generic digits the keys of
+// an activation vector crowd into a few dozen bins) and the barrier-separated LDS round
 // trips.  Each stage is therefore written for the fewest instructions per key: plain histogram
 // adds with the tie-storm handling hoisted out of the per-key path, branch-free clamped
 // loads, one compare per key on the usual path where no tie is split at the threshold.
