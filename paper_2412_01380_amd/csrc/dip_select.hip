@@ -411,10 +411,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     select_body<ITEMS>(p, sh);
 }
 
-constexpr int kUpdateBatch = 64;   // pieces per launch: they travel in the kernel arguments
+// pieces per launch: they travel in the kernel arguments (4 KB at most), and 80 is what a stack
+// of 40 layers asks for in one call
+constexpr int kUpdateBatch = 80;
 struct UpdateWork {
     UpdatePiece piece[kUpdateBatch];
 };
+static_assert(sizeof(UpdateWork) <= 4096, "kernel arguments are limited to 4 KB");
 
 template <int ITEMS>
 __global__ __launch_bounds__(kSelThreads) void update_batch_kernel(UpdateWork work) {
