@@ -100,10 +100,14 @@ def test_forward_uses_the_one_launch_form(D, d, f, fmt):
 
 @pytest.mark.parametrize("d,f,fmt,r", [(512, 1536, "f32", 0.5), (1000, 2056, "f32", 0.3),
                                        (1032, 1160, "bf16", 0.7), (2048, 5120, "int4", 0.3),
-                                       (3072, 8192, "bf16", 0.25)])
+                                       (3072, 8192, "bf16", 0.25),
+                                       # the widest instantiations: 32 keys per lane at point 2, 8 at point 1
+                                       (256, 32768, "f32", 0.3), (8192, 1024, "bf16", 0.2)])
 def test_stage_replay_random_tokens_dip_and_dipca(D, d, f, fmt, r):
     k_in, k_mid = max(1, round(r * d)), max(1, round(r * f))
     L = _layer(D, d, f, fmt, 2, k_in, k_mid)
+    assert D.dip_fused_launch_shape(L["mlp"].w_ug, k_in, bundled=True) is not None
+    assert D.dip_fused_launch_shape(L["mlp"].w_d, k_mid, bundled=False) is not None
     xs = studentt_tokens(3, d, seed=d)
     for t in range(3):
         _replay(D, L, xs[t], k_in, k_mid)
