@@ -655,7 +655,7 @@ int32_t batched_one(const dip_mlp* mlp, const BatchedPlan& pl, const float* X, i
         const bool mc = pt == 0 ? pl.mc1 : pl.mc2;
         uint32_t* rowmax = reinterpret_cast<uint32_t*>(base + pl.off_rmax) + 8 * pt;
         sp.rowmax_out = mc ? rowmax : nullptr;     // max |x| per row, for the matrix-core product's scaling
-        if ((st = check_hip(launch_select(sp, hs, q.kind), "forward_batched: select"))) return st;
+        if ((st = check_hip(launch_select_rows(sp, hs, q.kind), "forward_batched: select"))) return st;
         // union of the row masks, its index list and the row multipliers
         UnionParams up;
         std::memset(&up, 0, sizeof(up));

@@ -76,6 +76,35 @@ __device__ __forceinline__ uint32_t bisect_quotient(uint32_t lo, uint32_t hi, fl
     return lo;
 }
 
+// The keys that tie with the k-th largest score, and those above it (Eq. 10 without a division
+// per key, see the head of this file): Tk is the k-th largest key (bits(p) << 1), M = ||v||_inf.
+// Leaves K_lo, K_hi alone when M is 0 (all scores are 0).
+__device__ __forceinline__ void score_window(uint32_t Tk, float M, int lane, uint32_t& K_lo, uint32_t& K_hi) {
+    if (!(M > 0.f)) return;
+    const uint32_t Tb = Tk >> 1;
+    const float Ts = __fdiv_rn(__uint_as_float(Tb), M);
+    constexpr uint32_t kInf = 0x7f800000u;
+    const int64_t cand = (int64_t)Tb + lane - 31;
+    const uint32_t cb = cand < 0 ? 0u : (cand > (int64_t)kInf ? kInf : (uint32_t)cand);
+    const float qc = __fdiv_rn(__uint_as_float(cb), M);
+    const uint64_t ge = __ballot(qc >= Ts), gt = __ballot(qc > Ts);   // lane 31 is T_p: in ge
+    const uint32_t c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cb);
+    uint32_t Plo, Phi;
+    if ((ge & 1ull) && c0 > 0u) {
+        Plo = bisect_quotient<false>(0u, c0, M, Ts);
+    } else {
+        // (ge is never empty for finite inputs: lane 31 holds T_p itself)
+        Plo = ge ? (uint32_t)__builtin_amdgcn_readlane((int)cb, __builtin_ctzll(ge)) : Tb;
+    }
+    if (gt == 0ull) {
+        Phi = bisect_quotient<true>(Tb + 1u, kInf, M, Ts);
+    } else {
+        Phi = (uint32_t)__builtin_amdgcn_readlane((int)cb, __builtin_ctzll(gt));
+    }
+    K_lo = Plo << 1;
+    K_hi = Phi << 1;
+}
+
 // Per-tile counts of the keys in [K_lo, K_hi) (low 16 bits) and >= K_hi (high 16 bits), their
 // exclusive prefix over the tiles in index order (lane j of each wavefront returns the prefix
 // of the wavefront's tile in slot j), and the totals.
@@ -245,32 +274,7 @@ __global__ __launch_bounds__(kSelThreads) void fused_kernel(FusedParams fp) {
 
     // keys in [K_lo, K_hi) tie at the k-th largest score, keys >= K_hi lie above it
     uint32_t K_lo = Tk, K_hi = Tk + 1u;
-    if (q.score_bits) {
-        if (M > 0.f) {
-            const uint32_t Tb = Tk >> 1;
-            const float Ts = __fdiv_rn(__uint_as_float(Tb), M);
-            constexpr uint32_t kInf = 0x7f800000u;
-            const int64_t cand = (int64_t)Tb + lane - 31;
-            const uint32_t cb = cand < 0 ? 0u : (cand > (int64_t)kInf ? kInf : (uint32_t)cand);
-            const float qc = __fdiv_rn(__uint_as_float(cb), M);
-            const uint64_t ge = __ballot(qc >= Ts), gt = __ballot(qc > Ts);   // lane 31 is T_p: in ge
-            const uint32_t c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cb);
-            uint32_t Plo, Phi;
-            if ((ge & 1ull) && c0 > 0u) {
-                Plo = bisect_quotient<false>(0u, c0, M, Ts);
-            } else {
-                // (ge is never empty for finite inputs: lane 31 holds T_p itself)
-                Plo = ge ? (uint32_t)__builtin_amdgcn_readlane((int)cb, __builtin_ctzll(ge)) : Tb;
-            }
-            if (gt == 0ull) {
-                Phi = bisect_quotient<true>(Tb + 1u, kInf, M, Ts);
-            } else {
-                Phi = (uint32_t)__builtin_amdgcn_readlane((int)cb, __builtin_ctzll(gt));
-            }
-            K_lo = Plo << 1;
-            K_hi = Phi << 1;
-        }
-    }
+    if (q.score_bits) score_window(Tk, M, lane, K_lo, K_hi);
 
     // ---- this workgroup's share of the list ---------------------------------------------------
     // Counts of the keys >= K_lo per (slot, wavefront) tile and their running sums in index
@@ -406,6 +410,106 @@ hipError_t launch_lpr(const FusedParams& fp, const GemvShape& s, hipStream_t str
     return hipErrorInvalidConfiguration;
 }
 
+
+#if DIP_FUSED_NSEG == 1 && DIP_FUSED_DTYPE == 0
+// ---- row selections of a small batch --------------------------------------------------------
+// One workgroup per row runs the head above on that row -- keys without a division, one
+// histogram pass, the exact-tie window -- and leaves the row's mask words (and the bit pattern
+// of max |v|, which the matrix-core product scales by).  No lists: the union kernel builds
+// them from the masks of all rows.
+struct RowsShared {
+    HeadShared head;
+    uint32_t mwords[kMaxWords];
+    uint32_t wave_cnt[kWaves];
+};
+
+template <int ITEMS>
+__global__ __launch_bounds__(kSelThreads) void rows_select_kernel(SelectParams p) {
+    __shared__ __align__(16) RowsShared sh;
+    HeadShared& hs = sh.head;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nwords = (p.n + 31) >> 5;
+    const float* vrow = p.v + (size_t)blockIdx.x * p.v_row_stride;
+    uint32_t* mrow = p.mask_out + (size_t)blockIdx.x * p.words_row_stride;
+    int phase = 0;
+
+    float v[ITEMS];
+    uint32_t key[ITEMS];
+    {
+        const float* vp = vrow + tid;
+        const int full = p.n >> 10;     // slots that lie inside the vector entirely (wave-uniform)
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (j < full) {
+                v[j] = vp[j * kSelThreads];
+            } else {
+                const uint32_t i = (uint32_t)(j * kSelThreads + tid);
+                v[j] = 0.f;
+                if (i < (uint32_t)p.n) v[j] = vrow[i & (DIP_MAX_N - 1)];
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < kHeadHistWords / (2 * kSelThreads); ++b)
+        reinterpret_cast<uint2*>(hs.hist)[b * kSelThreads + tid] = make_uint2(0u, 0u);
+    hs.cw[tid] = (p.score_bits && tid < nwords) ? p.score_bits[tid] : 0u;
+    {
+        float vmax = 0.f;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) vmax = fmaxf(vmax, fabsf(v[j]));
+        vmax = wave_max_nonneg(vmax);
+        if (lane == 0) hs.wave_max[wave] = vmax;
+    }
+    __syncthreads();
+    const float M = row_max_nonneg(hs.wave_max[lane & (kWaves - 1)]);
+    if (p.rowmax_out && tid == 0) p.rowmax_out[blockIdx.x] = __float_as_uint(M);
+    if (p.score_bits) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const float a = fabsf(v[j]);
+            const uint32_t c = (hs.cw[j * (kSelThreads / 32) + (tid >> 5)] >> (tid & 31)) & 1u;
+            key[j] = __float_as_uint(c ? a : __fmul_rn(a, p.gamma)) << 1;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) key[j] = __float_as_uint(fabsf(v[j])) << 1;
+    }
+    uint32_t Tk, need;
+    block_select_largest_near_max<ITEMS>(key, __float_as_uint(M) << 1, (uint32_t)p.k, hs, phase, Tk, need);
+    uint32_t K_lo = Tk, K_hi = Tk + 1u;
+    if (p.score_bits) score_window(Tk, M, lane, K_lo, K_hi);
+
+    // how many keys reach K_lo: exactly k means no tie is split at the threshold
+    uint32_t n_wave = 0u;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) n_wave += (uint32_t)__popcll(__ballot(key[j] >= K_lo));
+    if (lane == 0) sh.wave_cnt[wave] = n_wave;
+    __syncthreads();
+    uint32_t n_ge = 0u;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) n_ge += sh.wave_cnt[w];
+    const bool fast = n_ge == (uint32_t)p.k;
+    uint32_t take = 0u, eq_seen = 0u;
+    if (!fast) {
+        uint32_t totals;
+        const int pre = (int)tile_prefix_window<ITEMS>(key, K_lo, K_hi, hs, phase, totals);
+        take = (uint32_t)p.k > (totals >> 16) ? (uint32_t)p.k - (totals >> 16) : 0u;
+        eq_seen = (uint32_t)pre;
+    }
+    int my_word = 0;
+    MaskWords<0, ITEMS>::run(key, K_lo, K_hi, fast, take, eq_seen, 0, 1, my_word);
+    if (lane < 2 * ITEMS)
+        sh.mwords[((lane >> 1) * (kSelThreads / 32) + wave * 2 + (lane & 1)) & (kMaxWords - 1)] = (uint32_t)my_word;
+    __syncthreads();
+    if (tid < nwords) mrow[tid] = sh.mwords[tid];
+}
+
+template <int ITEMS>
+hipError_t launch_rows_items(const SelectParams& p, hipStream_t stream, int pk) {
+    return launch_timed(rows_select_kernel<ITEMS>, dim3(p.rows), dim3(kSelThreads), stream, pk, p);
+}
+#endif
+
 #ifndef DIP_FUSED_NSEG
 #error "compile with -DDIP_FUSED_NSEG=1 or 2 and -DDIP_FUSED_DTYPE=0, 1 or 2"
 #endif
@@ -426,5 +530,23 @@ hipError_t DIP_FUSED_NAME(DIP_FUSED_NSEG, DIP_FUSED_DTYPE)(const FusedParams& fp
     return launch_lpr<q4n_t, DIP_FUSED_NSEG>(fp, s, stream, pk);
 #endif
 }
+
+
+#if DIP_FUSED_NSEG == 1 && DIP_FUSED_DTYPE == 0
+hipError_t launch_select_rows(const SelectParams& p, hipStream_t stream, int pk) {
+    if (!p.v || !p.mask_out || p.rows < 1 || p.n < 1 || p.n > DIP_MAX_N || p.k < 1 || p.k > p.n)
+        return hipErrorInvalidValue;
+    const int items = (p.n + kSelThreads - 1) / kSelThreads;
+    if (items <= 2) return launch_rows_items<2>(p, stream, pk);
+    if (items <= 4) return launch_rows_items<4>(p, stream, pk);
+    if (items <= 6) return launch_rows_items<6>(p, stream, pk);
+    if (items <= 8) return launch_rows_items<8>(p, stream, pk);
+    if (items <= 11) return launch_rows_items<11>(p, stream, pk);
+    if (items <= 14) return launch_rows_items<14>(p, stream, pk);
+    if (items <= 18) return launch_rows_items<18>(p, stream, pk);
+    if (items <= 24) return launch_rows_items<24>(p, stream, pk);
+    return launch_rows_items<32>(p, stream, pk);
+}
+#endif
 
 }  // namespace dip

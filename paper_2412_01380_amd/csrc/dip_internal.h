@@ -70,6 +70,9 @@ struct SelectParams {
 };
 
 hipError_t launch_select(const SelectParams& p, hipStream_t stream, int prof_kind);
+// The row selections of a small batch (rows >= 1, one workgroup per row): mask_out and, if
+// given, rowmax_out only; every other output of SelectParams must be off.
+hipError_t launch_select_rows(const SelectParams& p, hipStream_t stream, int prof_kind);
 
 // Cache updates of several caches in one launch, one workgroup each (nothing in the token
 // that produced the masks waits for them).
